@@ -1,0 +1,155 @@
+/*
+ * symi.h - C ABI of the Symi MoE hot path for MI355X (gfx950).
+ *
+ * One GPU's share of one adaptive-replication MoE training iteration
+ * (Symi, arXiv 2504.19925, Sec. 3.2, Fig. 5 steps 1-8):
+ *
+ *   forward    symi_route -> symi_dispatch -> symi_expert_fwd -> symi_combine
+ *   backward   symi_combine_bwd -> symi_expert_bwd -> symi_dispatch_bwd -> symi_route_bwd
+ *   optimizer  symi_place (next placement, Algorithm 1) -> symi_adam_to_replicas
+ *
+ * Conventions
+ *   - Every function returns 0 (SYMI_OK) or a negative error code; symi_last_error()
+ *     returns a description of the most recent failure on the calling thread.
+ *   - Unless a parameter says "host", every pointer is a DEVICE pointer owned by the
+ *     caller, valid until the work enqueued on `stream` has finished.  The library
+ *     allocates nothing and never synchronises with the host inside these calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - `cfg` and `hp` are HOST pointers, read during the call only.
+ *   - Activations and slot weights are fp32 or bf16 according to cfg->dtype; routing
+ *     data, gradients of the weights and the Adam state are always fp32; all index
+ *     arrays are int32.  Matrices are row-major, the last index contiguous.
+ *   - Notation (paper Table 2): E expert classes, S_tot = s*N replica slots, N
+ *     optimizer partitions, T tokens, k choices per token, A = T*k assignments,
+ *     d model width, f FFN width, P_e = 3*d*f parameters per expert.
+ *   - Shape limits checked by symi_validate: 1 <= k <= min(E, 16), E <= 1024,
+ *     E <= S_tot <= 4096, P_e divisible by N, 0 <= shard < N; d, f and P_e/N
+ *     multiples of 8.
+ */
+#ifndef SYMI_H
+#define SYMI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SYMI_OK = 0, SYMI_EINVAL = -1, SYMI_EUNSUPPORTED = -2, SYMI_EHIP = -3 };
+enum { SYMI_F32 = 0, SYMI_BF16 = 1 };
+
+typedef struct symi_cfg {
+  int T;      /* tokens in this GPU's batch */
+  int E;      /* expert classes */
+  int k;      /* choices per token (top-k) */
+  int d;      /* model width */
+  int f;      /* FFN (hidden) width of one SwiGLU expert */
+  int S_tot;  /* replica slots = slots per rank * ranks (eq. (2): sum_i r_i = sN) */
+  int N;      /* optimizer partitions (ranks) */
+  int shard;  /* which partition this GPU owns, 0 <= shard < N */
+  int dtype;  /* SYMI_F32 or SYMI_BF16: activations and slot weights */
+  int renorm; /* 1: the k gates of a token are renormalised to sum to 1 */
+} symi_cfg;
+
+typedef struct symi_adam {
+  float lr, beta1, beta2, eps, weight_decay, grad_scale;
+  int step; /* 1-based iteration count used for bias correction */
+} symi_adam;
+
+/* Host-only checks of a configuration (no GPU needed). */
+int symi_validate(const symi_cfg* cfg);
+/* Bytes of device workspace `ws` that symi_dispatch / symi_expert_fwd /
+ * symi_expert_bwd need for this configuration (0 if cfg is invalid). */
+size_t symi_workspace_bytes(const symi_cfg* cfg);
+const char* symi_last_error(void);
+
+/* Sec. 2.1 (top-k gating) + Sec. 3.2 step 1 (per-class token count, the popularity
+ * array kept by the Layer Metadata Store).
+ *   logits [T,E] f32 in.  idx [T,k] i32 out: the k best classes of each token, best
+ *   first, equal scores resolved towards the lower class index.  gate [T,k] f32 out:
+ *   softmax over all E classes evaluated at idx, divided by their sum if cfg->renorm.
+ *   hist [E] i32 out: number of (token, choice) pairs per class; sums to T*k.       */
+int symi_route(const symi_cfg* cfg, const float* logits, int32_t* idx, float* gate,
+               int32_t* hist, void* stream);
+
+/* Backward of symi_route's gate: dlogits [T,E] f32 out from dgate [T,k] f32. */
+int symi_route_bwd(const symi_cfg* cfg, const float* logits, const int32_t* idx,
+                   const float* gate, const float* dgate, float* dlogits, void* stream);
+
+/* Expert Placement Scheduler, Algorithm 1 (App. A.3; Sec. 3.4), in exact integer
+ * arithmetic: replicas proportional to popularity, at least one per class, exactly
+ * S_tot in total, same-class slots contiguous.  First extremum wins ties; an all-zero
+ * popularity is read as uniform.
+ *   popularity [E] i32 in (normally the previous iteration's hist).
+ *   counts [E] i32 out (r_i), placement [S_tot] i32 out (slot -> class),
+ *   first_slot [E+1] i32 out (prefix sums of counts).                               */
+int symi_place(const symi_cfg* cfg, const int32_t* popularity, int32_t* counts,
+               int32_t* placement, int32_t* first_slot, void* stream);
+/* Same computation on HOST pointers (the paper runs the scheduler on every rank's CPU). */
+int symi_place_host(const symi_cfg* cfg, const int32_t* popularity, int32_t* counts,
+                    int32_t* placement, int32_t* first_slot);
+
+/* Sec. 3.2 step 2: tokens go to their classes, and the rows of a class are spread over
+ * that class's replicas under the CURRENT placement (counts, first_slot).
+ *   Assignment a = t*k + j.  Rows are assignments in stable class order; replica i of
+ *   class e owns c_e*i/r_e .. c_e*(i+1)/r_e (integer division) of the class's c_e rows.
+ *   X [T,d] in; idx [T,k], hist [E] (this iteration's), counts [E], first_slot [E+1] in.
+ *   row_of_assign [A], assign_of_row [A], slot_offsets [S_tot+1] i32 out;
+ *   Xp [A,d] out: Xp[row] = X[assign_of_row[row] / k].                              */
+int symi_dispatch(const symi_cfg* cfg, const void* X, const int32_t* idx, const int32_t* hist,
+                  const int32_t* counts, const int32_t* first_slot, int32_t* row_of_assign,
+                  int32_t* assign_of_row, int32_t* slot_offsets, void* Xp, void* ws,
+                  void* stream);
+
+/* Backward of the gather: dX[t] = sum_j dXp[row_of_assign[t*k+j]] (j ascending). */
+int symi_dispatch_bwd(const symi_cfg* cfg, const void* dXp, const int32_t* row_of_assign,
+                      void* dX, void* stream);
+
+/* Expert SwiGLU FFN over replica slots (Sec. 2.1; the expert compute of Fig. 5).
+ * For slot q with rows [slot_offsets[q], slot_offsets[q+1]):
+ *   u = x Wg^T, v = x Wu^T, h = silu(u)*v, y = h Wd^T
+ *   W1_slots [S_tot,2f,d]: rows 0..f-1 = Wg, rows f..2f-1 = Wu; W2_slots [S_tot,d,f] = Wd.
+ *   UV [A,2f] (u | v), H [A,f] and Yp [A,d] out (UV and H are kept for the backward). */
+int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_t* slot_offsets,
+                    const void* W1_slots, const void* W2_slots, void* UV, void* H, void* Yp,
+                    void* ws, void* stream);
+
+/* Backward of symi_expert_fwd.  dXp [A,d] out.  dW1_class [E,2f,d], dW2_class [E,d,f]
+ * f32 out: the gradient of each class summed over ALL its rows, i.e. over all its
+ * replica slots (the intra-rank part of the gradient all-reduce of Sec. 4.1); a class
+ * without rows gets zeros.  first_slot [E+1] is the placement used by symi_dispatch. */
+int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
+                    const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
+                    const void* W1_slots, const void* W2_slots, void* dXp, float* dW1_class,
+                    float* dW2_class, void* ws, void* stream);
+
+/* Gate-weighted combine: Y[t] = sum_j gate[t,j] * Yp[row_of_assign[t*k+j]], j ascending,
+ * accumulated in fp32.  Y [T,d] out. */
+int symi_combine(const symi_cfg* cfg, const void* Yp, const int32_t* row_of_assign,
+                 const float* gate, void* Y, void* stream);
+
+/* Backward of symi_combine: dYp[row] = gate[t,j]*dY[t]; dgate[t,j] = <dY[t], Yp[row]>. */
+int symi_combine_bwd(const symi_cfg* cfg, const void* dY, const void* Yp,
+                     const int32_t* row_of_assign, const float* gate, void* dYp, float* dgate,
+                     void* stream);
+
+/* Sec. 3.2 steps 4-8 for optimizer partition cfg->shard (Symi Optimizer: static uniform
+ * partition, Sec. 3.1/3.3; weight communication phase, Sec. 4.4).  The flat parameter
+ * vector of a class is [W1 (2f*d) | W2 (d*f)]; partition n owns its range
+ * [n*P_e/N, (n+1)*P_e/N).  On that range, for every class: Adam with bias correction
+ * (eps outside the root, decoupled weight decay) on master_w, m, v [E, P_e/N] f32
+ * (in/out) from grad_scale * dW_class; then the fresh weights, rounded to nearest-even
+ * bf16 if cfg->dtype is bf16, are written into the same range of every slot
+ * first_slot_next[e] .. first_slot_next[e+1]-1 of W1_slots / W2_slots: the placement of
+ * the NEXT iteration.  Bytes written to slots are S_tot*P_e/N*sizeof(weight), whatever
+ * the placement.  hp is a HOST pointer. */
+int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp, const float* dW1_class,
+                          const float* dW2_class, float* master_w, float* m, float* v,
+                          const int32_t* first_slot_next, void* W1_slots, void* W2_slots,
+                          void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SYMI_H */

@@ -1,0 +1,27 @@
+"""MI355X-native hot path of Symi's adaptive MoE training step (one GPU's share).
+
+All computation happens in libsymi.so (hand-written HIP for gfx950, C ABI declared in
+include/symi.h).  This package only marshals arguments: torch tensors in, pointers out.
+"""
+from .binding import (  # noqa: F401
+    SymiCfg,
+    SymiAdam,
+    SymiError,
+    lib,
+    lib_path,
+    symi_validate,
+    symi_workspace_bytes,
+    symi_last_error,
+    symi_route,
+    symi_route_bwd,
+    symi_place,
+    symi_place_host,
+    symi_dispatch,
+    symi_dispatch_bwd,
+    symi_expert_fwd,
+    symi_expert_bwd,
+    symi_combine,
+    symi_combine_bwd,
+    symi_adam_to_replicas,
+    EXPORTS,
+)

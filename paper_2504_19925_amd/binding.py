@@ -1,0 +1,238 @@
+"""ctypes binding of libsymi.so: same names as the C ABI, argument marshalling only.
+
+Tensors must live on the GPU (except where the C function takes host pointers), be
+contiguous and have the dtype the header states; the current torch stream is passed
+through.  There is no fallback: if the library is missing or a call fails, SymiError
+is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = [
+    "symi_validate", "symi_workspace_bytes", "symi_last_error", "symi_route", "symi_route_bwd",
+    "symi_place", "symi_place_host", "symi_dispatch", "symi_dispatch_bwd", "symi_expert_fwd",
+    "symi_expert_bwd", "symi_combine", "symi_combine_bwd", "symi_adam_to_replicas",
+]
+
+
+class SymiError(RuntimeError):
+    pass
+
+
+class SymiCfg(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("T", "E", "k", "d", "f", "S_tot", "N", "shard", "dtype", "renorm")]
+
+    @classmethod
+    def make(cls, T, E, k, d, f, S_tot, N, shard=0, dtype="bf16", renorm=1):
+        return cls(T, E, k, d, f, S_tot, N, shard, {"f32": 0, "bf16": 1}[dtype], int(renorm))
+
+    @property
+    def A(self):
+        return self.T * self.k
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == 1 else torch.float32
+
+
+class SymiAdam(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("grad_scale", ctypes.c_float), ("step", ctypes.c_int)]
+
+
+def lib_path():
+    return os.path.join(_HERE, "libsymi.so")
+
+
+def lib():
+    """Loads libsymi.so once; raises if it has not been built."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise SymiError(f"{path} not found: build it with `python -m paper_2504_19925_amd.build`")
+        L = ctypes.CDLL(path)
+        vp, ip, fp = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+        cfgp = ctypes.POINTER(SymiCfg)
+        sig = {
+            "symi_validate": [cfgp],
+            "symi_route": [cfgp, fp, ip, fp, ip, vp],
+            "symi_route_bwd": [cfgp, fp, ip, fp, fp, fp, vp],
+            "symi_place": [cfgp, ip, ip, ip, ip, vp],
+            "symi_place_host": [cfgp, ip, ip, ip, ip],
+            "symi_dispatch": [cfgp, vp, ip, ip, ip, ip, ip, ip, ip, vp, vp, vp],
+            "symi_dispatch_bwd": [cfgp, vp, ip, vp, vp],
+            "symi_expert_fwd": [cfgp, vp, ip, vp, vp, vp, vp, vp, vp, vp],
+            "symi_expert_bwd": [cfgp, vp, vp, vp, vp, ip, ip, vp, vp, vp, fp, fp, vp, vp],
+            "symi_combine": [cfgp, vp, ip, fp, vp, vp],
+            "symi_combine_bwd": [cfgp, vp, vp, ip, fp, vp, fp, vp],
+            "symi_adam_to_replicas": [cfgp, ctypes.POINTER(SymiAdam), fp, fp, fp, fp, fp, ip, vp, vp, vp],
+        }
+        for name, args in sig.items():
+            fn = getattr(L, name)
+            fn.argtypes = args
+            fn.restype = ctypes.c_int
+        L.symi_workspace_bytes.argtypes = [cfgp]
+        L.symi_workspace_bytes.restype = ctypes.c_size_t
+        L.symi_last_error.argtypes = []
+        L.symi_last_error.restype = ctypes.c_char_p
+        _LIB = L
+    return _LIB
+
+
+def symi_last_error():
+    return lib().symi_last_error().decode()
+
+
+def _check(rc, who):
+    if rc != 0:
+        raise SymiError(f"{who} failed ({rc}): {symi_last_error()}")
+
+
+def _dev(t, dtype, name, numel=None):
+    if not isinstance(t, torch.Tensor):
+        raise SymiError(f"{name}: expected a torch tensor")
+    if not t.is_cuda:
+        raise SymiError(f"{name}: expected a GPU tensor")
+    if t.dtype != dtype:
+        raise SymiError(f"{name}: expected dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise SymiError(f"{name}: must be contiguous")
+    if numel is not None and t.numel() < numel:
+        raise SymiError(f"{name}: needs at least {numel} elements, has {t.numel()}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _host_i32(t, name, numel):
+    if t.is_cuda or t.dtype != torch.int32 or not t.is_contiguous() or t.numel() < numel:
+        raise SymiError(f"{name}: expected a contiguous CPU int32 tensor of >= {numel} elements")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+I32, F32 = torch.int32, torch.float32
+
+
+def symi_validate(cfg):
+    return lib().symi_validate(ctypes.byref(cfg))
+
+
+def symi_workspace_bytes(cfg):
+    return lib().symi_workspace_bytes(ctypes.byref(cfg))
+
+
+def symi_route(cfg, logits, idx, gate, hist):
+    _check(lib().symi_route(ctypes.byref(cfg), _dev(logits, F32, "logits", cfg.T * cfg.E),
+                            _dev(idx, I32, "idx", cfg.A), _dev(gate, F32, "gate", cfg.A),
+                            _dev(hist, I32, "hist", cfg.E), _stream()), "symi_route")
+
+
+def symi_route_bwd(cfg, logits, idx, gate, dgate, dlogits):
+    _check(lib().symi_route_bwd(ctypes.byref(cfg), _dev(logits, F32, "logits", cfg.T * cfg.E),
+                                _dev(idx, I32, "idx", cfg.A), _dev(gate, F32, "gate", cfg.A),
+                                _dev(dgate, F32, "dgate", cfg.A),
+                                _dev(dlogits, F32, "dlogits", cfg.T * cfg.E), _stream()),
+           "symi_route_bwd")
+
+
+def symi_place(cfg, popularity, counts, placement, first_slot):
+    _check(lib().symi_place(ctypes.byref(cfg), _dev(popularity, I32, "popularity", cfg.E),
+                            _dev(counts, I32, "counts", cfg.E),
+                            _dev(placement, I32, "placement", cfg.S_tot),
+                            _dev(first_slot, I32, "first_slot", cfg.E + 1), _stream()), "symi_place")
+
+
+def symi_place_host(cfg, popularity, counts, placement, first_slot):
+    _check(lib().symi_place_host(ctypes.byref(cfg), _host_i32(popularity, "popularity", cfg.E),
+                                 _host_i32(counts, "counts", cfg.E),
+                                 _host_i32(placement, "placement", cfg.S_tot),
+                                 _host_i32(first_slot, "first_slot", cfg.E + 1)), "symi_place_host")
+
+
+def symi_dispatch(cfg, X, idx, hist, counts, first_slot, row_of_assign, assign_of_row,
+                  slot_offsets, Xp, ws):
+    dt = cfg.torch_dtype
+    _check(lib().symi_dispatch(
+        ctypes.byref(cfg), _dev(X, dt, "X", cfg.T * cfg.d), _dev(idx, I32, "idx", cfg.A),
+        _dev(hist, I32, "hist", cfg.E), _dev(counts, I32, "counts", cfg.E),
+        _dev(first_slot, I32, "first_slot", cfg.E + 1),
+        _dev(row_of_assign, I32, "row_of_assign", cfg.A),
+        _dev(assign_of_row, I32, "assign_of_row", cfg.A),
+        _dev(slot_offsets, I32, "slot_offsets", cfg.S_tot + 1), _dev(Xp, dt, "Xp", cfg.A * cfg.d),
+        _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), "symi_dispatch")
+
+
+def symi_dispatch_bwd(cfg, dXp, row_of_assign, dX):
+    dt = cfg.torch_dtype
+    _check(lib().symi_dispatch_bwd(ctypes.byref(cfg), _dev(dXp, dt, "dXp", cfg.A * cfg.d),
+                                   _dev(row_of_assign, I32, "row_of_assign", cfg.A),
+                                   _dev(dX, dt, "dX", cfg.T * cfg.d), _stream()), "symi_dispatch_bwd")
+
+
+def symi_expert_fwd(cfg, Xp, slot_offsets, W1_slots, W2_slots, UV, H, Yp, ws):
+    dt = cfg.torch_dtype
+    nw = cfg.S_tot * cfg.d * cfg.f
+    _check(lib().symi_expert_fwd(
+        ctypes.byref(cfg), _dev(Xp, dt, "Xp", cfg.A * cfg.d),
+        _dev(slot_offsets, I32, "slot_offsets", cfg.S_tot + 1),
+        _dev(W1_slots, dt, "W1_slots", 2 * nw), _dev(W2_slots, dt, "W2_slots", nw),
+        _dev(UV, dt, "UV", cfg.A * 2 * cfg.f), _dev(H, dt, "H", cfg.A * cfg.f),
+        _dev(Yp, dt, "Yp", cfg.A * cfg.d), _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)),
+        _stream()), "symi_expert_fwd")
+
+
+def symi_expert_bwd(cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots, W2_slots, dXp,
+                    dW1_class, dW2_class, ws):
+    dt = cfg.torch_dtype
+    nw = cfg.S_tot * cfg.d * cfg.f
+    ne = cfg.E * cfg.d * cfg.f
+    _check(lib().symi_expert_bwd(
+        ctypes.byref(cfg), _dev(dYp, dt, "dYp", cfg.A * cfg.d), _dev(Xp, dt, "Xp", cfg.A * cfg.d),
+        _dev(UV, dt, "UV", cfg.A * 2 * cfg.f), _dev(H, dt, "H", cfg.A * cfg.f),
+        _dev(slot_offsets, I32, "slot_offsets", cfg.S_tot + 1),
+        _dev(first_slot, I32, "first_slot", cfg.E + 1), _dev(W1_slots, dt, "W1_slots", 2 * nw),
+        _dev(W2_slots, dt, "W2_slots", nw), _dev(dXp, dt, "dXp", cfg.A * cfg.d),
+        _dev(dW1_class, F32, "dW1_class", 2 * ne), _dev(dW2_class, F32, "dW2_class", ne),
+        _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), "symi_expert_bwd")
+
+
+def symi_combine(cfg, Yp, row_of_assign, gate, Y):
+    dt = cfg.torch_dtype
+    _check(lib().symi_combine(ctypes.byref(cfg), _dev(Yp, dt, "Yp", cfg.A * cfg.d),
+                              _dev(row_of_assign, I32, "row_of_assign", cfg.A),
+                              _dev(gate, F32, "gate", cfg.A), _dev(Y, dt, "Y", cfg.T * cfg.d),
+                              _stream()), "symi_combine")
+
+
+def symi_combine_bwd(cfg, dY, Yp, row_of_assign, gate, dYp, dgate):
+    dt = cfg.torch_dtype
+    _check(lib().symi_combine_bwd(
+        ctypes.byref(cfg), _dev(dY, dt, "dY", cfg.T * cfg.d), _dev(Yp, dt, "Yp", cfg.A * cfg.d),
+        _dev(row_of_assign, I32, "row_of_assign", cfg.A), _dev(gate, F32, "gate", cfg.A),
+        _dev(dYp, dt, "dYp", cfg.A * cfg.d), _dev(dgate, F32, "dgate", cfg.A), _stream()),
+        "symi_combine_bwd")
+
+
+def symi_adam_to_replicas(cfg, hp, dW1_class, dW2_class, master_w, m, v, first_slot_next,
+                          W1_slots, W2_slots):
+    dt = cfg.torch_dtype
+    ne = cfg.E * cfg.d * cfg.f
+    nw = cfg.S_tot * cfg.d * cfg.f
+    per = cfg.E * (3 * cfg.d * cfg.f // cfg.N)
+    _check(lib().symi_adam_to_replicas(
+        ctypes.byref(cfg), ctypes.byref(hp), _dev(dW1_class, F32, "dW1_class", 2 * ne),
+        _dev(dW2_class, F32, "dW2_class", ne), _dev(master_w, F32, "master_w", per),
+        _dev(m, F32, "m", per), _dev(v, F32, "v", per),
+        _dev(first_slot_next, I32, "first_slot_next", cfg.E + 1),
+        _dev(W1_slots, dt, "W1_slots", 2 * nw), _dev(W2_slots, dt, "W2_slots", nw), _stream()),
+        "symi_adam_to_replicas")

@@ -1,0 +1,78 @@
+// Host-side parts of libsymi: configuration checks, error text, workspace layout.
+#include <stdarg.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace symi {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int check_cfg(const symi_cfg* c, const char* who) {
+  if (!c) {
+    set_error("%s: cfg is NULL", who);
+    return SYMI_EINVAL;
+  }
+#define BAD(cond, msg)                   \
+  if (cond) {                            \
+    set_error("%s: %s", who, msg);       \
+    return SYMI_EINVAL;                  \
+  }
+  BAD(c->T < 0, "T < 0");
+  BAD(c->E < 1 || c->E > 1024, "E outside [1, 1024]");
+  BAD(c->k < 1 || c->k > c->E || c->k > 16, "k outside [1, min(E, 16)]");
+  BAD(c->d < 8 || c->d % 8, "d must be a positive multiple of 8");
+  BAD(c->f < 8 || c->f % 8, "f must be a positive multiple of 8");
+  // Sec. 3.4: at least one instance per expert class, so the slot budget must cover E.
+  BAD(c->S_tot < c->E, "S_tot < E: every class needs one slot");
+  BAD(c->S_tot > 4096, "S_tot > 4096");
+  BAD(c->N < 1, "N < 1");
+  BAD(c->shard < 0 || c->shard >= c->N, "shard outside [0, N)");
+  BAD(c->dtype != SYMI_F32 && c->dtype != SYMI_BF16, "dtype must be SYMI_F32 or SYMI_BF16");
+  BAD(c->renorm != 0 && c->renorm != 1, "renorm must be 0 or 1");
+  long long Pe = 3LL * c->d * c->f;
+  BAD(Pe % c->N, "P_e = 3*d*f is not divisible by N");
+  BAD((Pe / c->N) % 8, "P_e / N is not a multiple of 8");
+  BAD((long long)c->T * c->k > 0x7fffffffLL / 2, "T*k too large for int32 indexing");
+#undef BAD
+  return SYMI_OK;
+}
+
+WsLayout ws_layout(const symi_cfg* c) {
+  WsLayout L;
+  const size_t A = (size_t)c->T * c->k;
+  const size_t w = c->dtype == SYMI_BF16 ? 2 : 4;
+  const size_t nblk = (A + DISPATCH_CHUNK - 1) / DISPATCH_CHUNK;
+  const size_t mtiles = A / GEMM_BM + c->S_tot + 1;
+  size_t off = 0;
+  L.blk_counts = off;
+  off += align_up((nblk + 1) * c->E * sizeof(int32_t), 256);
+  L.tile_map = off;
+  off += align_up((4 + 4 * mtiles) * sizeof(int32_t), 256);
+  L.duv = off;
+  off += align_up(A * 2 * c->f * w, 256);
+  L.total = off + 256;
+  return L;
+}
+
+}  // namespace symi
+
+extern "C" {
+
+int symi_validate(const symi_cfg* cfg) { return symi::check_cfg(cfg, "symi_validate"); }
+
+size_t symi_workspace_bytes(const symi_cfg* cfg) {
+  if (symi::check_cfg(cfg, "symi_workspace_bytes") != SYMI_OK) return 0;
+  return symi::ws_layout(cfg).total;
+}
+
+const char* symi_last_error(void) { return symi::g_err; }
+
+}  // extern "C"

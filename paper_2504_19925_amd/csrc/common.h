@@ -1,0 +1,62 @@
+// Internal helpers shared by the HIP translation units of libsymi (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "symi.h"
+
+namespace symi {
+
+void set_error(const char* fmt, ...);
+int check_cfg(const symi_cfg* cfg, const char* who);
+void launch_fill_i32(int32_t* p, int n, int32_t val, hipStream_t st);
+
+#define SYMI_REQUIRE(cond, who, msg)                      \
+  do {                                                    \
+    if (!(cond)) {                                        \
+      symi::set_error("%s: %s", who, msg);                \
+      return SYMI_EINVAL;                                 \
+    }                                                     \
+  } while (0)
+
+#define SYMI_LAUNCH_CHECK(who)                                            \
+  do {                                                                    \
+    hipError_t e_ = hipGetLastError();                                    \
+    if (e_ != hipSuccess) {                                               \
+      symi::set_error("%s: launch failed: %s", who, hipGetErrorString(e_)); \
+      return SYMI_EHIP;                                                   \
+    }                                                                     \
+  } while (0)
+
+static inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+// bf16 <-> fp32 on raw 16-bit patterns.  Round to nearest, ties to even; NaN kept quiet.
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) {
+  return __uint_as_float(((uint32_t)h) << 16);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Workspace layout (byte offsets inside the caller's `ws`), one place for all users.
+struct WsLayout {
+  size_t blk_counts;   // dispatch: [nblk][E] i32 per-block class counts, then bases
+  size_t tile_map;     // expert fwd/bwd: m-tile table, see gemm.hip
+  size_t duv;          // expert bwd: dUV [A,2f] in the activation dtype
+  size_t total;
+};
+WsLayout ws_layout(const symi_cfg* cfg);
+
+constexpr int DISPATCH_CHUNK = 1024;  // assignments ranked by one workgroup
+constexpr int GEMM_BM = 128;          // rows of one m-tile in the tile map
+
+}  // namespace symi

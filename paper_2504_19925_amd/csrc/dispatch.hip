@@ -1,0 +1,335 @@
+// symi_dispatch / symi_dispatch_bwd / symi_combine / symi_combine_bwd: the token ->
+// replica permutation of paper Sec. 3.2 step 2 and the data movement around the expert
+// FFN (the all-to-all scatter/gather of Sec. 2.1, which on one GPU is a local
+// permutation).
+//
+// The permutation is a stable counting sort of the A = T*k assignments by class, made
+// deterministic without ordered atomics:
+//   1. every workgroup counts the classes of its chunk of DISPATCH_CHUNK assignments;
+//   2. one workgroup per class turns the per-chunk counts into exclusive bases (class
+//      offset O_e + rows of that class in earlier chunks) and writes the class's
+//      entries of slot_offsets from O_e, c_e and the placement;
+//   3. every workgroup ranks its chunk again: inside a wavefront the rank among equal
+//      classes is a popcount over a match mask built from ballots, across wavefronts
+//      and passes it is a small LDS prefix.
+// Row moves are 16-byte vector loads/stores, one row spread over consecutive lanes.
+#include "common.h"
+
+namespace symi {
+
+constexpr int DT = 256;                      // threads per workgroup
+constexpr int DPASS = DISPATCH_CHUNK / DT;   // passes of 256 assignments per chunk
+
+__global__ __launch_bounds__(DT) void chunk_count_kernel(const int32_t* __restrict__ cls, int A,
+                                                         int E, int32_t* __restrict__ blk_counts) {
+  extern __shared__ int32_t cnt_s[];
+  for (int i = threadIdx.x; i < E; i += DT) cnt_s[i] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * DISPATCH_CHUNK;
+#pragma unroll
+  for (int p = 0; p < DPASS; ++p) {
+    const int a = base + p * DT + threadIdx.x;
+    if (a < A && (unsigned)cls[a] < (unsigned)E) atomicAdd(&cnt_s[cls[a]], 1);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < E; i += DT) blk_counts[(size_t)blockIdx.x * E + i] = cnt_s[i];
+}
+
+// grid = E workgroups; workgroup e scans column e of blk_counts in place into bases.
+__global__ __launch_bounds__(DT) void chunk_scan_kernel(int32_t* __restrict__ blk_counts, int nblk,
+                                                        int E, int S, int A,
+                                                        const int32_t* __restrict__ hist,
+                                                        const int32_t* __restrict__ counts,
+                                                        const int32_t* __restrict__ first_slot,
+                                                        int32_t* __restrict__ slot_offsets) {
+  __shared__ int32_t wsum[DT / 64];
+  __shared__ int32_t carry_s;
+  __shared__ int32_t red[DT / 64];
+  const int e = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // class offset O_e = rows of all lower classes
+  int part = 0;
+  for (int i = threadIdx.x; i < e; i += DT) part += hist[i];
+  for (int m = 32; m >= 1; m >>= 1) part += __shfl_xor(part, m, 64);
+  if (lane == 0) red[wave] = part;
+  __syncthreads();
+  int O_e = 0;
+  for (int w = 0; w < DT / 64; ++w) O_e += red[w];
+  if (threadIdx.x == 0) carry_s = O_e;
+  __syncthreads();
+
+  for (int b0 = 0; b0 < nblk; b0 += DT) {
+    const int b = b0 + threadIdx.x;
+    const int c = b < nblk ? blk_counts[(size_t)b * E + e] : 0;
+    int incl = c;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int before = carry_s;
+    for (int w = 0; w < wave; ++w) before += wsum[w];
+    if (b < nblk) blk_counts[(size_t)b * E + e] = before + incl - c;
+    __syncthreads();
+    if (threadIdx.x == DT - 1) carry_s = before + incl;
+    __syncthreads();
+  }
+
+  // replica i of class e owns rows O_e + floor(i*c_e/r_e) .. O_e + floor((i+1)*c_e/r_e)
+  const int r = counts[e], c_e = hist[e], F = first_slot[e];
+  for (int i = threadIdx.x; i < r; i += DT)
+    slot_offsets[F + i] = O_e + (int)(((long long)i * c_e) / r);
+  if (e == E - 1 && threadIdx.x == 0) slot_offsets[S] = A;
+}
+
+__global__ __launch_bounds__(DT) void chunk_rank_kernel(const int32_t* __restrict__ cls, int A, int E,
+                                                        const int32_t* __restrict__ bases,
+                                                        int32_t* __restrict__ row_of_assign,
+                                                        int32_t* __restrict__ assign_of_row) {
+  extern __shared__ int32_t sm[];
+  int32_t* running = sm;           // [E] rows of class e already placed by this workgroup (+ base)
+  int32_t* wcnt = sm + E;          // [4][E] per-wavefront counts of the current pass
+  constexpr int NW = DT / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < E; i += DT) running[i] = bases[(size_t)blockIdx.x * E + i];
+  for (int i = threadIdx.x; i < NW * E; i += DT) wcnt[i] = 0;
+  __syncthreads();
+  int ebits = 0;
+  while ((1 << ebits) < E) ++ebits;
+  const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  const int base = blockIdx.x * DISPATCH_CHUNK;
+
+  for (int p = 0; p < DPASS; ++p) {
+    const int a = base + p * DT + threadIdx.x;
+    const int c_raw = a < A ? cls[a] : 0;
+    const bool valid = a < A && (unsigned)c_raw < (unsigned)E;   // a class outside [0,E) is skipped
+    const int c = valid ? c_raw : 0;
+    // lanes of this wavefront that hold the same class
+    unsigned long long mask = __ballot(valid);
+    for (int b = 0; b < ebits; ++b) {
+      const unsigned long long bal = __ballot((c >> b) & 1);
+      mask &= ((c >> b) & 1) ? bal : ~bal;
+    }
+    const int rank_in_wave = __popcll(mask & lt);
+    if (valid && rank_in_wave == 0) wcnt[wave * E + c] = __popcll(mask);
+    __syncthreads();
+    if (valid) {
+      int row = running[c] + rank_in_wave;
+      for (int w = 0; w < wave; ++w) row += wcnt[w * E + c];
+      row_of_assign[a] = row;
+      if ((unsigned)row < (unsigned)A) assign_of_row[row] = a;   // false only if hist disagrees with idx
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < E; i += DT) {
+      int s = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) { s += wcnt[w * E + i]; wcnt[w * E + i] = 0; }
+      running[i] += s;
+    }
+    __syncthreads();
+  }
+}
+
+// dst[row] = src[map[row] / div] for rows of `vec_per_row` 16-byte pieces.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ src,
+                                                          uint4* __restrict__ dst,
+                                                          const int32_t* __restrict__ map, int div,
+                                                          long long n_vec, int vec_per_row) {
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n_vec;
+       i += (long long)gridDim.x * 256) {
+    const long long row = i / vec_per_row;
+    const int c = (int)(i - row * vec_per_row);
+    const long long s = map[row] / div;
+    dst[i] = src[s * vec_per_row + c];
+  }
+}
+
+struct f8 { float v[8]; };
+
+template <bool BF16>
+__device__ __forceinline__ int load_piece(const void* p, long long piece, float (&out)[8]) {
+  if (BF16) {
+    const uint4 q = reinterpret_cast<const uint4*>(p)[piece];
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[2 * i] = __uint_as_float(w[i] << 16);
+      out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+    return 8;
+  } else {
+    const float4 q = reinterpret_cast<const float4*>(p)[piece];
+    out[0] = q.x; out[1] = q.y; out[2] = q.z; out[3] = q.w;
+    return 4;
+  }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void store_piece(void* p, long long piece, const float (&in)[8]) {
+  if (BF16) {
+    uint4 q;
+    q.x = pack_bf16x2(in[0], in[1]); q.y = pack_bf16x2(in[2], in[3]);
+    q.z = pack_bf16x2(in[4], in[5]); q.w = pack_bf16x2(in[6], in[7]);
+    reinterpret_cast<uint4*>(p)[piece] = q;
+  } else {
+    reinterpret_cast<float4*>(p)[piece] = make_float4(in[0], in[1], in[2], in[3]);
+  }
+}
+
+// out[t] = sum_j w[t,j] * src[row_of_assign[t*k+j]]   (w == nullptr: plain sum)
+template <bool BF16>
+__global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ src,
+                                                      const int32_t* __restrict__ roa,
+                                                      const float* __restrict__ w,
+                                                      void* __restrict__ out, int T, int k,
+                                                      int pieces_per_row) {
+  constexpr int PW = BF16 ? 8 : 4;
+  const long long n = (long long)T * pieces_per_row;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n;
+       i += (long long)gridDim.x * 256) {
+    const long long t = i / pieces_per_row;
+    const int c = (int)(i - t * pieces_per_row);
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j = 0; j < k; ++j) {
+      const long long row = roa[t * k + j];
+      const float g = w ? w[t * k + j] : 1.f;
+      float x[8];
+      load_piece<BF16>(src, row * pieces_per_row + c, x);
+#pragma unroll
+      for (int q = 0; q < PW; ++q) acc[q] = fmaf(g, x[q], acc[q]);
+    }
+    store_piece<BF16>(out, i, acc);
+  }
+}
+
+// One wavefront per token: dYp[row] = gate*dY[t] and dgate[t,j] = <dY[t], Yp[row]>.
+template <bool BF16>
+__global__ __launch_bounds__(256) void combine_bwd_kernel(const void* __restrict__ dY,
+                                                          const void* __restrict__ Yp,
+                                                          const int32_t* __restrict__ roa,
+                                                          const float* __restrict__ gate,
+                                                          void* __restrict__ dYp,
+                                                          float* __restrict__ dgate, int T, int k,
+                                                          int pieces_per_row) {
+  constexpr int PW = BF16 ? 8 : 4;
+  const int lane = threadIdx.x & 63;
+  const long long wave0 = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  for (long long t = wave0; t < T; t += (long long)gridDim.x * 4) {
+    for (int j = 0; j < k; ++j) {
+      const long long row = roa[t * k + j];
+      const float g = gate[t * k + j];
+      float dot = 0.f;
+      for (int c = lane; c < pieces_per_row; c += 64) {
+        float dy[8], yp[8], o[8];
+        load_piece<BF16>(dY, t * pieces_per_row + c, dy);
+        load_piece<BF16>(Yp, row * pieces_per_row + c, yp);
+#pragma unroll
+        for (int q = 0; q < PW; ++q) {
+          dot = fmaf(dy[q], yp[q], dot);
+          o[q] = g * dy[q];
+        }
+        store_piece<BF16>(dYp, row * pieces_per_row + c, o);
+      }
+      for (int m = 32; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
+      if (lane == 0) dgate[t * k + j] = dot;
+    }
+  }
+}
+
+static int grid_for(long long work_items, int per_block) {
+  long long g = (work_items + per_block - 1) / per_block;
+  if (g < 1) g = 1;
+  if (g > 16384) g = 16384;
+  return (int)g;
+}
+
+}  // namespace symi
+
+using namespace symi;
+
+extern "C" int symi_dispatch(const symi_cfg* cfg, const void* X, const int32_t* idx,
+                             const int32_t* hist, const int32_t* counts, const int32_t* first_slot,
+                             int32_t* row_of_assign, int32_t* assign_of_row, int32_t* slot_offsets,
+                             void* Xp, void* ws, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_dispatch")) return rc;
+  SYMI_REQUIRE(hist && counts && first_slot && slot_offsets && ws, "symi_dispatch", "NULL pointer");
+  SYMI_REQUIRE(cfg->T == 0 || (X && idx && row_of_assign && assign_of_row && Xp), "symi_dispatch",
+               "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  const int E = cfg->E, A = cfg->T * cfg->k;
+  const WsLayout L = ws_layout(cfg);
+  int32_t* blk = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.blk_counts);
+  const int nblk = cdiv(A, DISPATCH_CHUNK);
+  if (nblk > 0)
+    chunk_count_kernel<<<nblk, DT, E * sizeof(int32_t), st>>>(idx, A, E, blk);
+  chunk_scan_kernel<<<E, DT, 0, st>>>(blk, nblk, E, cfg->S_tot, A, hist, counts, first_slot,
+                                      slot_offsets);
+  if (nblk > 0) {
+    chunk_rank_kernel<<<nblk, DT, (size_t)(1 + DT / 64) * E * sizeof(int32_t), st>>>(
+        idx, A, E, blk, row_of_assign, assign_of_row);
+    const int w = cfg->dtype == SYMI_BF16 ? 2 : 4;
+    const int vpr = cfg->d * w / 16;
+    const long long nvec = (long long)A * vpr;
+    gather_rows_kernel<<<grid_for(nvec, 256 * 4), 256, 0, st>>>(
+        static_cast<const uint4*>(X), static_cast<uint4*>(Xp), assign_of_row, cfg->k, nvec, vpr);
+  }
+  SYMI_LAUNCH_CHECK("symi_dispatch");
+  return SYMI_OK;
+}
+
+extern "C" int symi_dispatch_bwd(const symi_cfg* cfg, const void* dXp, const int32_t* row_of_assign,
+                                 void* dX, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_dispatch_bwd")) return rc;
+  if (cfg->T == 0) return SYMI_OK;
+  SYMI_REQUIRE(dXp && row_of_assign && dX, "symi_dispatch_bwd", "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  if (cfg->dtype == SYMI_BF16) {
+    const int ppr = cfg->d / 8;
+    combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+        dXp, row_of_assign, nullptr, dX, cfg->T, cfg->k, ppr);
+  } else {
+    const int ppr = cfg->d / 4;
+    combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+        dXp, row_of_assign, nullptr, dX, cfg->T, cfg->k, ppr);
+  }
+  SYMI_LAUNCH_CHECK("symi_dispatch_bwd");
+  return SYMI_OK;
+}
+
+extern "C" int symi_combine(const symi_cfg* cfg, const void* Yp, const int32_t* row_of_assign,
+                            const float* gate, void* Y, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_combine")) return rc;
+  if (cfg->T == 0) return SYMI_OK;
+  SYMI_REQUIRE(Yp && row_of_assign && gate && Y, "symi_combine", "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  if (cfg->dtype == SYMI_BF16) {
+    const int ppr = cfg->d / 8;
+    combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+        Yp, row_of_assign, gate, Y, cfg->T, cfg->k, ppr);
+  } else {
+    const int ppr = cfg->d / 4;
+    combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+        Yp, row_of_assign, gate, Y, cfg->T, cfg->k, ppr);
+  }
+  SYMI_LAUNCH_CHECK("symi_combine");
+  return SYMI_OK;
+}
+
+extern "C" int symi_combine_bwd(const symi_cfg* cfg, const void* dY, const void* Yp,
+                                const int32_t* row_of_assign, const float* gate, void* dYp,
+                                float* dgate, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_combine_bwd")) return rc;
+  if (cfg->T == 0) return SYMI_OK;
+  SYMI_REQUIRE(dY && Yp && row_of_assign && gate && dYp && dgate, "symi_combine_bwd", "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  if (cfg->dtype == SYMI_BF16)
+    combine_bwd_kernel<true><<<grid_for(cfg->T, 4), 256, 0, st>>>(dY, Yp, row_of_assign, gate, dYp,
+                                                                 dgate, cfg->T, cfg->k, cfg->d / 8);
+  else
+    combine_bwd_kernel<false><<<grid_for(cfg->T, 4), 256, 0, st>>>(dY, Yp, row_of_assign, gate, dYp,
+                                                                  dgate, cfg->T, cfg->k, cfg->d / 4);
+  SYMI_LAUNCH_CHECK("symi_combine_bwd");
+  return SYMI_OK;
+}

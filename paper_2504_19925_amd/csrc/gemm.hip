@@ -1,0 +1,561 @@
+// symi_expert_fwd / symi_expert_bwd: the expert SwiGLU FFN over replica slots as
+// variable-group grouped GEMMs (paper Sec. 2.1; the expert compute of Fig. 5; the
+// intra-rank part of the replica gradient reduction of Sec. 4.1 is fused into the
+// weight-gradient GEMM, which sums over every row of a class at once).
+//
+// Six products share one tiled kernel (bf16 inputs, fp32 accumulation on the gfx950
+// MFMA 32x32x16 bf16 instruction; a plain-FMA twin serves fp32 configurations):
+//   FWD1   [u|v] = Xp  * W1^T      + SwiGLU epilogue writing u, v and h = silu(u)*v
+//   FWD2   Yp    = H   * W2^T
+//   BWD_DH dh    = dYp * W2        + epilogue turning dh into du, dv (never stored as dh)
+//   BWD_DX dXp   = dUV * W1
+//   WGRAD2 dW2_e = dYp^T * H       over all rows of class e
+//   WGRAD1 dW1_e = dUV^T * Xp      over all rows of class e
+// The first four have a variable number of rows per group (one group per slot); a small
+// kernel turns slot_offsets into a table of 128-row m-tiles so that no workgroup spans
+// two slots.  The last two have a variable reduction length (the rows of a class).
+//
+// Tiles are staged in LDS with the reduction index contiguous, whatever the operand's
+// layout in HBM; operands whose reduction index is strided in memory are transposed in
+// registers (2x8 blocks) on their way into LDS.  The MFMA is issued with the weight
+// tile as its first operand, so a lane ends up with 4 consecutive output columns of one
+// output row and writes them with one vector store.
+#include "common.h"
+
+namespace symi {
+
+enum { FWD1 = 0, FWD2 = 1, BWD_DH = 2, BWD_DX = 3, WGRAD2 = 4, WGRAD1 = 5 };
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+struct GemmParams {
+  const void* A;       // activations (left operand source)
+  const void* B;       // weights per slot, or the second activation for weight gradients
+  void* C;             // main output
+  const void* UV;      // BWD_DH: saved u|v
+  void* UVout;         // FWD1: u|v out
+  void* H;             // FWD1: h out
+  const int32_t* tile_map;      // [4 + 4*i]: header {n_tiles}, then {row0, row1, slot, -}
+  const int32_t* slot_offsets;  // weight gradients: class row ranges
+  const int32_t* first_slot;
+  long long b_group_stride;     // elements between consecutive slots' weights
+  long long c_group_stride;     // elements between consecutive classes' gradients
+  int M;   // fixed row count of the output (weight gradients)
+  int N;   // output columns (FWD1: f, counted once)
+  int K;   // reduction length when fixed
+  int d, f;
+};
+
+__device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
+__device__ __forceinline__ float sigmoid_f(float u) { return 1.f / (1.f + expf(-u)); }
+
+// ---------------------------------------------------------------- m-tile table
+__global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ slot_offsets,
+                                                       int S, int32_t* __restrict__ map) {
+  __shared__ int32_t part[256];
+  const int tid = threadIdx.x;
+  const int per = (S + 255) / 256;
+  const int q0 = tid * per, q1 = min(S, q0 + per);
+  int mine = 0;
+  for (int q = q0; q < q1; ++q) mine += (slot_offsets[q + 1] - slot_offsets[q] + GEMM_BM - 1) / GEMM_BM;
+  part[tid] = mine;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {  // Hillis-Steele inclusive scan
+    const int add = tid >= o ? part[tid - o] : 0;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  int t = part[tid] - mine;
+  if (tid == 255) map[0] = part[255];
+  for (int q = q0; q < q1; ++q) {
+    const int b = slot_offsets[q], e = slot_offsets[q + 1];
+    for (int r = b; r < e; r += GEMM_BM, ++t) {
+      map[4 + 4 * t + 0] = r;
+      map[4 + 4 * t + 1] = min(e, r + GEMM_BM);
+      map[4 + 4 * t + 2] = q;
+      map[4 + 4 * t + 3] = 0;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- bf16 MFMA kernel
+constexpr int BM = 128, BN = 128, BK = 64, LDK = BK + 8;  // LDS row stride in bf16 (pad: no bank conflicts on 16-byte reads)
+constexpr int WM = 64, WN = 64;                           // per-wavefront output tile
+constexpr int GT = 256;                                   // 4 wavefronts, 2 x 2
+
+// Stage a [128 x 64] tile whose reduction index is contiguous in memory.
+// rowptr(i) returns the address of element (tile row i, reduction index 0) or nullptr.
+struct KcStage { uint4 v[4]; };
+// Stage a tile whose reduction index is strided: 2 (k) x 8 (r) blocks, two per thread.
+struct KsStage { uint4 v[2][2]; };
+
+template <int MODE>
+__global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][BM * LDK];  // [stage][A|B]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  constexpr bool VARM = MODE <= BWD_DX;
+  constexpr bool A_KC = VARM;                       // left operand reduction-contiguous
+  constexpr bool B_KC = MODE == FWD1 || MODE == FWD2;
+
+  int row0, row1, group, n0, kbeg = 0, K;
+  if (VARM) {
+    const int mt = blockIdx.y;
+    if (mt >= p.tile_map[0]) return;
+    row0 = p.tile_map[4 + 4 * mt];
+    row1 = p.tile_map[4 + 4 * mt + 1];
+    group = p.tile_map[4 + 4 * mt + 2];
+    K = p.K;
+  } else {
+    group = blockIdx.z;
+    row0 = blockIdx.y * BM;
+    row1 = min(p.M, row0 + BM);
+    kbeg = p.slot_offsets[p.first_slot[group]];
+    K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
+  }
+  // FWD1 covers BN/2 hidden units per tile: each wavefront's 64 columns are 32 gate
+  // columns followed by the 32 up columns of the same hidden units.
+  n0 = blockIdx.x * (MODE == FWD1 ? BN / 2 : BN);
+
+  const uint16_t* A = static_cast<const uint16_t*>(p.A);
+  const uint16_t* B = static_cast<const uint16_t*>(p.B) + (VARM ? (long long)group * p.b_group_stride : 0);
+  const long long lda = MODE == FWD1 ? p.d : MODE == FWD2 ? p.f : MODE == BWD_DH ? p.d
+                        : MODE == BWD_DX ? 2LL * p.f : MODE == WGRAD2 ? p.d : 2LL * p.f;
+  const long long ldb = MODE == FWD1 ? p.d : MODE == FWD2 ? p.f : MODE == BWD_DH ? p.f
+                        : MODE == BWD_DX ? p.d : MODE == WGRAD2 ? p.f : p.d;
+
+  // ---- per-thread source addresses
+  // reduction-contiguous operands: piece (row = i*32 + tid/8, k-chunk = tid%8)
+  const int pr = tid >> 3, pc = tid & 7;
+  const uint16_t* a_kc[4];
+  const uint16_t* b_kc[4];
+  if (A_KC) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = row0 + i * 32 + pr;
+      a_kc[i] = r < row1 ? A + (long long)r * lda + pc * 8 : nullptr;
+    }
+  }
+  if (B_KC) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = i * 32 + pr;  // tile row of the weight operand
+      long long wrow;
+      bool ok;
+      if (MODE == FWD1) {
+        const int hu = n0 + (j >> 6) * 32 + (j & 31);   // hidden unit
+        ok = hu < p.f;
+        wrow = ((j >> 5) & 1) ? (long long)p.f + hu : hu;
+      } else {
+        wrow = n0 + j;
+        ok = wrow < p.N;
+      }
+      b_kc[i] = ok ? B + wrow * ldb + pc * 8 : nullptr;
+    }
+  }
+  // reduction-strided operands: block (r-chunk = tid%16, k-pair = tid/16 + 16*i)
+  const int rb = tid & 15, kp0 = tid >> 4;
+  const bool a_ks_ok = !A_KC && (row0 + rb * 8 < row1);
+  const bool b_ks_ok = !B_KC && (n0 + rb * 8 < p.N);
+  const uint16_t* a_ks = A_KC ? nullptr : A + (long long)kbeg * lda + row0 + rb * 8;
+  const uint16_t* b_ks = B_KC ? nullptr
+                              : (VARM ? B + n0 + rb * 8 : B + (long long)kbeg * ldb + n0 + rb * 8);
+
+  KcStage sa_kc, sb_kc;
+  KsStage sa_ks, sb_ks;
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  auto g_load = [&](int k0) {
+    if (A_KC) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        sa_kc.v[i] = (a_kc[i] && k0 + pc * 8 < K) ? *reinterpret_cast<const uint4*>(a_kc[i] + k0) : zero4;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int k = k0 + 2 * (kp0 + 16 * i) + j;
+          sa_ks.v[i][j] = (a_ks_ok && k < K) ? *reinterpret_cast<const uint4*>(a_ks + (long long)k * lda) : zero4;
+        }
+    }
+    if (B_KC) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        sb_kc.v[i] = (b_kc[i] && k0 + pc * 8 < K) ? *reinterpret_cast<const uint4*>(b_kc[i] + k0) : zero4;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int k = k0 + 2 * (kp0 + 16 * i) + j;
+          sb_ks.v[i][j] = (b_ks_ok && k < K) ? *reinterpret_cast<const uint4*>(b_ks + (long long)k * ldb) : zero4;
+        }
+    }
+  };
+
+  auto store_ks = [&](uint16_t* tile, const KsStage& s) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint32_t lo[4] = {s.v[i][0].x, s.v[i][0].y, s.v[i][0].z, s.v[i][0].w};
+      const uint32_t hi[4] = {s.v[i][1].x, s.v[i][1].y, s.v[i][1].z, s.v[i][1].w};
+      const int kk = 2 * (kp0 + 16 * i);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t even = (lo[c] & 0xffffu) | (hi[c] << 16);          // r = 2c
+        const uint32_t odd = (lo[c] >> 16) | (hi[c] & 0xffff0000u);       // r = 2c+1
+        *reinterpret_cast<uint32_t*>(tile + (rb * 8 + 2 * c) * LDK + kk) = even;
+        *reinterpret_cast<uint32_t*>(tile + (rb * 8 + 2 * c + 1) * LDK + kk) = odd;
+      }
+    }
+  };
+  auto store_kc = [&](uint16_t* tile, const KcStage& s) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<uint4*>(tile + (i * 32 + pr) * LDK + pc * 8) = s.v[i];
+  };
+  auto s_store = [&](int stage) {
+    if (A_KC) store_kc(lds[stage][0], sa_kc); else store_ks(lds[stage][0], sa_ks);
+    if (B_KC) store_kc(lds[stage][1], sb_kc); else store_ks(lds[stage][1], sb_ks);
+  };
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = (K + BK - 1) / BK;
+  if (nk > 0) {
+    g_load(0);
+    s_store(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) g_load((kt + 1) * BK);
+    const uint16_t* At = lds[cur][0] + (wm * WM + (lane & 31)) * LDK + (lane >> 5) * 8;
+    const uint16_t* Bt = lds[cur][1] + (wn * WN + (lane & 31)) * LDK + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 af[2], bf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = *reinterpret_cast<const bf16x8*>(At + i * 32 * LDK + ks * 16);
+        bf[i] = *reinterpret_cast<const bf16x8*>(Bt + i * 32 * LDK + ks * 16);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) s_store(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: lane owns output row (lane%32) and 4 consecutive columns per r/4
+  const int colq = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = row0 + wm * WM + i * 32 + (lane & 31);
+    if (row >= row1) continue;
+    if (MODE == FWD1) {
+      uint16_t* UVo = static_cast<uint16_t*>(p.UVout);
+      uint16_t* Ho = static_cast<uint16_t*>(p.H);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int hu = n0 + wn * 32 + g * 8 + colq;
+        if (hu >= p.f) continue;
+        float u[4], v[4], h[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          u[c] = acc[i][0][g * 4 + c];
+          v[c] = acc[i][1][g * 4 + c];
+          h[c] = silu_f(u[c]) * v[c];
+        }
+        const long long o = (long long)row * 2 * p.f + hu;
+        *reinterpret_cast<uint2*>(UVo + o) = make_uint2(pack_bf16x2(u[0], u[1]), pack_bf16x2(u[2], u[3]));
+        *reinterpret_cast<uint2*>(UVo + o + p.f) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+        *reinterpret_cast<uint2*>(Ho + (long long)row * p.f + hu) =
+            make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn * WN + j * 32 + g * 8 + colq;
+          if (col >= p.N) continue;
+          const float x0 = acc[i][j][g * 4], x1 = acc[i][j][g * 4 + 1], x2 = acc[i][j][g * 4 + 2],
+                      x3 = acc[i][j][g * 4 + 3];
+          if (MODE == FWD2 || MODE == BWD_DX) {
+            uint16_t* Co = static_cast<uint16_t*>(p.C);
+            *reinterpret_cast<uint2*>(Co + (long long)row * p.N + col) =
+                make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
+          } else if (MODE == BWD_DH) {
+            const uint16_t* UVi = static_cast<const uint16_t*>(p.UV);
+            uint16_t* Co = static_cast<uint16_t*>(p.C);  // dUV
+            const long long o = (long long)row * 2 * p.f + col;
+            const uint2 uu = *reinterpret_cast<const uint2*>(UVi + o);
+            const uint2 vv = *reinterpret_cast<const uint2*>(UVi + o + p.f);
+            const float dh[4] = {x0, x1, x2, x3};
+            const float u[4] = {__uint_as_float(uu.x << 16), __uint_as_float(uu.x & 0xffff0000u),
+                                __uint_as_float(uu.y << 16), __uint_as_float(uu.y & 0xffff0000u)};
+            const float v[4] = {__uint_as_float(vv.x << 16), __uint_as_float(vv.x & 0xffff0000u),
+                                __uint_as_float(vv.y << 16), __uint_as_float(vv.y & 0xffff0000u)};
+            float du[4], dv[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const float sg = sigmoid_f(u[c]);
+              du[c] = dh[c] * v[c] * sg * (1.f + u[c] * (1.f - sg));
+              dv[c] = dh[c] * u[c] * sg;
+            }
+            *reinterpret_cast<uint2*>(Co + o) = make_uint2(pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3]));
+            *reinterpret_cast<uint2*>(Co + o + p.f) = make_uint2(pack_bf16x2(dv[0], dv[1]), pack_bf16x2(dv[2], dv[3]));
+          } else {  // weight gradients, fp32
+            float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride;
+            *reinterpret_cast<float4*>(Co + (long long)row * p.N + col) = make_float4(x0, x1, x2, x3);
+          }
+        }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- fp32 FMA twin
+// Same six products for fp32 activations/weights: 64x64 output tile, 16-deep reduction
+// steps, each thread a 4x4 micro-tile, plain FMAs in fp32.
+constexpr int FB = 64, FK = 16;
+
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
+  __shared__ float As[FK][FB + 4];
+  __shared__ float Bs[FK][FB + 4];
+  const int tid = threadIdx.x;
+  constexpr bool VARM = MODE <= BWD_DX;
+  int row0, row1, group, kbeg = 0, K;
+  if (VARM) {
+    // fp32 tiles are 64 rows: each 128-row entry of the table is walked in two halves
+    const int mt = blockIdx.y >> 1;
+    if (mt >= p.tile_map[0]) return;
+    row0 = p.tile_map[4 + 4 * mt] + (blockIdx.y & 1) * FB;
+    row1 = p.tile_map[4 + 4 * mt + 1];
+    if (row0 >= row1) return;
+    row1 = min(row1, row0 + FB);
+    group = p.tile_map[4 + 4 * mt + 2];
+    K = p.K;
+  } else {
+    group = blockIdx.z;
+    row0 = blockIdx.y * FB;
+    row1 = min(p.M, row0 + FB);
+    kbeg = p.slot_offsets[p.first_slot[group]];
+    K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
+  }
+  const int n0 = blockIdx.x * (MODE == FWD1 ? FB / 2 : FB);
+  const float* A = static_cast<const float*>(p.A);
+  const float* B = static_cast<const float*>(p.B) + (VARM ? (long long)group * p.b_group_stride : 0);
+  const long long d = p.d, f = p.f;
+
+  // element (tile row i, reduction index k) of each operand, or 0 outside
+  auto a_at = [&](int i, int k) -> float {
+    const int r = row0 + i;
+    if (r >= row1 || k >= K) return 0.f;
+    switch (MODE) {
+      case FWD1: return A[r * d + k];
+      case FWD2: return A[r * f + k];
+      case BWD_DH: return A[r * d + k];
+      case BWD_DX: return A[r * 2 * f + k];
+      case WGRAD2: return A[(long long)(kbeg + k) * d + r];
+      default: return A[(long long)(kbeg + k) * 2 * f + r];
+    }
+  };
+  auto b_at = [&](int j, int k) -> float {
+    if (k >= K) return 0.f;
+    switch (MODE) {
+      case FWD1: {  // tile columns 0..31 gate, 32..63 up of hidden units n0..n0+31
+        const int hu = n0 + (j & 31);
+        if (hu >= f) return 0.f;
+        return B[((j >> 5) ? f + hu : hu) * d + k];
+      }
+      case FWD2: return n0 + j < p.N ? B[(long long)(n0 + j) * f + k] : 0.f;
+      case BWD_DH: return n0 + j < p.N ? B[(long long)k * f + n0 + j] : 0.f;
+      case BWD_DX: return n0 + j < p.N ? B[(long long)k * d + n0 + j] : 0.f;
+      case WGRAD2: return n0 + j < p.N ? B[(long long)(kbeg + k) * f + n0 + j] : 0.f;
+      default: return n0 + j < p.N ? B[(long long)(kbeg + k) * d + n0 + j] : 0.f;
+    }
+  };
+  constexpr bool A_KC = VARM, B_KC = MODE == FWD1 || MODE == FWD2;
+
+  float acc[4][4] = {};
+  const int ty = tid >> 4, tx = tid & 15;  // rows ty*4.., cols tx + 16*c (FWD1 pairs gate/up)
+  for (int k0 = 0; k0 < K; k0 += FK) {
+    for (int e = tid; e < FB * FK; e += 256) {
+      // walk the operand along its contiguous index for coalescing
+      const int ai = A_KC ? e / FK : e % FB, ak = A_KC ? e % FK : e / FB;
+      As[ak][ai] = a_at(ai, k0 + ak);
+      const int bj = B_KC ? e / FK : e % FB, bk = B_KC ? e % FK : e / FB;
+      Bs[bk][bj] = b_at(bj, k0 + bk);
+    }
+    __syncthreads();
+    // two-level summation: each 16-deep partial sum is formed on its own and then added,
+    // which keeps the rounding error of long reductions (weight gradients) near sqrt(K/16)
+    float part[4][4] = {};
+#pragma unroll
+    for (int k = 0; k < FK; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) b[c] = Bs[k][tx + 16 * c];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) part[i][c] = fmaf(a[i], b[c], part[i][c]);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[i][c] += part[i][c];
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = row0 + ty * 4 + i;
+    if (row >= row1) continue;
+    if (MODE == FWD1) {
+      // columns tx, tx+16 are gate of hidden units n0+tx, n0+tx+16; tx+32, tx+48 their up
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const int hu = n0 + tx + 16 * c;
+        if (hu >= f) continue;
+        const float u = acc[i][c], v = acc[i][c + 2];
+        float* UVo = static_cast<float*>(p.UVout);
+        UVo[row * 2 * f + hu] = u;
+        UVo[row * 2 * f + f + hu] = v;
+        static_cast<float*>(p.H)[row * f + hu] = silu_f(u) * v;
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int col = n0 + tx + 16 * c;
+        if (col >= p.N) continue;
+        const float x = acc[i][c];
+        if (MODE == FWD2 || MODE == BWD_DX) {
+          static_cast<float*>(p.C)[(long long)row * p.N + col] = x;
+        } else if (MODE == BWD_DH) {
+          const float* UVi = static_cast<const float*>(p.UV);
+          const float u = UVi[row * 2 * f + col], v = UVi[row * 2 * f + f + col];
+          const float sg = sigmoid_f(u);
+          float* Co = static_cast<float*>(p.C);
+          Co[row * 2 * f + col] = x * v * sg * (1.f + u * (1.f - sg));
+          Co[row * 2 * f + f + col] = x * u * sg;
+        } else {
+          (static_cast<float*>(p.C) + (long long)group * p.c_group_stride)[(long long)row * p.N + col] = x;
+        }
+      }
+    }
+  }
+}
+
+template <int MODE>
+static void launch_gemm(const symi_cfg* cfg, const GemmParams& p, int n_cols, int max_mtiles,
+                        hipStream_t st) {
+  if (cfg->dtype == SYMI_BF16) {
+    const int bn = MODE == FWD1 ? BN / 2 : BN;
+    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? max_mtiles : cdiv(p.M, BM), MODE <= BWD_DX ? 1 : cfg->E);
+    gemm_bf16_kernel<MODE><<<grid, GT, 0, st>>>(p);
+  } else {
+    const int bn = MODE == FWD1 ? FB / 2 : FB;
+    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 2 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : cfg->E);
+    gemm_f32_kernel<MODE><<<grid, 256, 0, st>>>(p);
+  }
+}
+
+}  // namespace symi
+
+using namespace symi;
+
+extern "C" int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_t* slot_offsets,
+                               const void* W1_slots, const void* W2_slots, void* UV, void* H,
+                               void* Yp, void* ws, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_expert_fwd")) return rc;
+  const long long A = (long long)cfg->T * cfg->k;
+  if (A == 0) return SYMI_OK;
+  SYMI_REQUIRE(Xp && slot_offsets && W1_slots && W2_slots && UV && H && Yp && ws, "symi_expert_fwd",
+               "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  const WsLayout L = ws_layout(cfg);
+  int32_t* map = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.tile_map);
+  const int max_mtiles = (int)(A / GEMM_BM) + cfg->S_tot;
+  tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, cfg->S_tot, map);
+
+  GemmParams p = {};
+  p.tile_map = map;
+  p.d = cfg->d;
+  p.f = cfg->f;
+  // u|v = Xp W1^T, h = silu(u)*v
+  p.A = Xp; p.B = W1_slots; p.UVout = UV; p.H = H;
+  p.b_group_stride = 2LL * cfg->f * cfg->d;
+  p.N = cfg->f; p.K = cfg->d;
+  launch_gemm<FWD1>(cfg, p, cfg->f, max_mtiles, st);
+  // Yp = h W2^T
+  p.A = H; p.B = W2_slots; p.C = Yp;
+  p.b_group_stride = (long long)cfg->d * cfg->f;
+  p.N = cfg->d; p.K = cfg->f;
+  launch_gemm<FWD2>(cfg, p, cfg->d, max_mtiles, st);
+  SYMI_LAUNCH_CHECK("symi_expert_fwd");
+  return SYMI_OK;
+}
+
+extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
+                               const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
+                               const void* W1_slots, const void* W2_slots, void* dXp,
+                               float* dW1_class, float* dW2_class, void* ws, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_expert_bwd")) return rc;
+  const long long A = (long long)cfg->T * cfg->k;
+  SYMI_REQUIRE(slot_offsets && first_slot && dW1_class && dW2_class && ws, "symi_expert_bwd",
+               "NULL pointer");
+  SYMI_REQUIRE(A == 0 || (dYp && Xp && UV && H && W1_slots && W2_slots && dXp), "symi_expert_bwd",
+               "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  const WsLayout L = ws_layout(cfg);
+  int32_t* map = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.tile_map);
+  void* dUV = static_cast<char*>(ws) + L.duv;
+  const int max_mtiles = (int)(A / GEMM_BM) + cfg->S_tot;
+
+  GemmParams p = {};
+  p.tile_map = map;
+  p.slot_offsets = slot_offsets;
+  p.first_slot = first_slot;
+  p.d = cfg->d;
+  p.f = cfg->f;
+  if (A > 0) {
+    tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, cfg->S_tot, map);
+    // dh = dYp W2, then du, dv
+    p.A = dYp; p.B = W2_slots; p.C = dUV; p.UV = UV;
+    p.b_group_stride = (long long)cfg->d * cfg->f;
+    p.N = cfg->f; p.K = cfg->d;
+    launch_gemm<BWD_DH>(cfg, p, cfg->f, max_mtiles, st);
+    // dXp = dUV W1
+    p.A = dUV; p.B = W1_slots; p.C = dXp;
+    p.b_group_stride = 2LL * cfg->f * cfg->d;
+    p.N = cfg->d; p.K = 2 * cfg->f;
+    launch_gemm<BWD_DX>(cfg, p, cfg->d, max_mtiles, st);
+  }
+  // class gradients (classes without rows get zeros: their reduction is empty)
+  p.A = dYp; p.B = H; p.C = dW2_class;
+  p.c_group_stride = (long long)cfg->d * cfg->f;
+  p.M = cfg->d; p.N = cfg->f;
+  launch_gemm<WGRAD2>(cfg, p, cfg->f, 0, st);
+  p.A = dUV; p.B = Xp; p.C = dW1_class;
+  p.c_group_stride = 2LL * cfg->f * cfg->d;
+  p.M = 2 * cfg->f; p.N = cfg->d;
+  launch_gemm<WGRAD1>(cfg, p, cfg->d, 0, st);
+  SYMI_LAUNCH_CHECK("symi_expert_bwd");
+  return SYMI_OK;
+}

@@ -1,0 +1,261 @@
+// symi_route / symi_route_bwd: top-k gating with the per-class popularity histogram
+// (paper Sec. 2.1 and Sec. 3.2 step 1).
+//
+// A token's logits row is shared by a group of G lanes (G a power of two, G*4*NV >= E),
+// each lane holding NV float4 pieces, so that global loads are coalesced 16-byte
+// accesses and the arg-max of each top-k round is a log2(G)-step butterfly inside the
+// 64-wide wavefront.  A wavefront serves 64/G tokens at a time.  Ties go to the lower
+// class index because every comparison orders (value, -index) pairs.  The histogram is
+// accumulated with integer atomics (LDS per workgroup, then one global add per class
+// and workgroup): integer sums do not depend on the order of the adds.
+#include <float.h>
+#include <limits.h>
+
+#include "common.h"
+
+namespace symi {
+
+constexpr int ROUTE_THREADS = 256;
+constexpr int MAX_K = 16;
+
+__global__ void fill_i32_kernel(int32_t* p, int n, int32_t val) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = val;
+}
+
+void launch_fill_i32(int32_t* p, int n, int32_t val, hipStream_t st) {
+  if (n > 0) fill_i32_kernel<<<cdiv(n, 256), 256, 0, st>>>(p, n, val);
+}
+
+template <int NV>
+__device__ __forceinline__ void load_row(const float* __restrict__ row, int E, int G, int g,
+                                         bool valid, float (&z)[NV * 4]) {
+  const bool vec_ok = (E & 3) == 0;
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int col0 = (v * G + g) * 4;
+    if (valid && vec_ok && col0 + 3 < E) {
+      const float4 q = *reinterpret_cast<const float4*>(row + col0);
+      z[v * 4 + 0] = q.x; z[v * 4 + 1] = q.y; z[v * 4 + 2] = q.z; z[v * 4 + 3] = q.w;
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        z[v * 4 + c] = (valid && col0 + c < E) ? row[col0 + c] : -INFINITY;
+    }
+  }
+}
+
+// Softmax statistics of the row held by a lane group: max and sum of exp(z - max).
+template <int NV>
+__device__ __forceinline__ void row_stats(const float (&z)[NV * 4], int E, int G, int g,
+                                          float& zmax, float& zsum) {
+  float mx = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < NV * 4; ++c) mx = fmaxf(mx, z[c]);
+  for (int m = G >> 1; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < NV * 4; ++c) {
+    const int col = ((c >> 2) * G + g) * 4 + (c & 3);
+    if (col < E) s += expf(z[c] - mx);
+  }
+  for (int m = G >> 1; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
+  zmax = mx;
+  zsum = s;
+}
+
+template <int NV>
+__global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
+    const float* __restrict__ logits, int32_t* __restrict__ idx, float* __restrict__ gate,
+    int32_t* __restrict__ hist, int T, int E, int k, int G, int renorm) {
+  extern __shared__ int32_t hist_s[];
+  for (int i = threadIdx.x; i < E; i += ROUTE_THREADS) hist_s[i] = 0;
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane & (G - 1), sub = lane / G, tpw = 64 / G;
+  const int tpb = (ROUTE_THREADS / 64) * tpw;
+
+  for (long long t0 = (long long)blockIdx.x * tpb; t0 < T; t0 += (long long)gridDim.x * tpb) {
+    const long long t = t0 + wave * tpw + sub;
+    const bool valid = t < T;
+    float z[NV * 4];
+    load_row<NV>(logits + (valid ? t : 0) * E, E, G, g, valid, z);
+    float zmax, zsum;
+    row_stats<NV>(z, E, G, g, zmax, zsum);
+
+    unsigned taken = 0;
+    float pj[MAX_K];
+    int ij[MAX_K];
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAX_K; ++j) {
+      pj[j] = 0.f;
+      ij[j] = 0;
+      if (j < k) {
+        float bv = -INFINITY;
+        int bi = INT_MAX;
+#pragma unroll
+        for (int c = 0; c < NV * 4; ++c) {
+          const int col = ((c >> 2) * G + g) * 4 + (c & 3);
+          const bool ok = col < E && !((taken >> c) & 1u);
+          if (ok && (z[c] > bv || (z[c] == bv && col < bi))) { bv = z[c]; bi = col; }
+        }
+        for (int m = G >> 1; m >= 1; m >>= 1) {
+          const float ov = __shfl_xor(bv, m, 64);
+          const int oi = __shfl_xor(bi, m, 64);
+          if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        // the lane that owns the winner retires it
+        const int vec = bi >> 2;
+        if (bi != INT_MAX && (vec & (G - 1)) == g) taken |= 1u << (((vec / G) << 2) | (bi & 3));
+        pj[j] = expf(bv - zmax) / zsum;
+        ij[j] = bi;
+        psum += pj[j];
+      }
+    }
+    if (valid) {
+#pragma unroll
+      for (int j = 0; j < MAX_K; ++j) {
+        if (j < k && g == (j & (G - 1))) {
+          idx[t * k + j] = ij[j];
+          gate[t * k + j] = renorm ? pj[j] / psum : pj[j];
+          if ((unsigned)ij[j] < (unsigned)E) atomicAdd(&hist_s[ij[j]], 1);  // false only for NaN rows
+        }
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < E; i += ROUTE_THREADS)
+    if (hist_s[i]) atomicAdd(&hist[i], hist_s[i]);
+}
+
+template <int NV>
+__global__ __launch_bounds__(ROUTE_THREADS) void route_bwd_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ idx,
+    const float* __restrict__ gate, const float* __restrict__ dgate,
+    float* __restrict__ dlogits, int T, int E, int k, int G, int renorm) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane & (G - 1), sub = lane / G, tpw = 64 / G;
+  const int tpb = (ROUTE_THREADS / 64) * tpw;
+
+  for (long long t0 = (long long)blockIdx.x * tpb; t0 < T; t0 += (long long)gridDim.x * tpb) {
+    const long long t = t0 + wave * tpw + sub;
+    const bool valid = t < T;
+    const float* row = logits + (valid ? t : 0) * E;
+    float z[NV * 4];
+    load_row<NV>(row, E, G, g, valid, z);
+    float zmax, zsum;
+    row_stats<NV>(z, E, G, g, zmax, zsum);
+
+    int ij[MAX_K];
+    float ps[MAX_K], dg[MAX_K];
+    float ssum = 0.f, dot = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAX_K; ++j) {
+      ij[j] = -1; ps[j] = 0.f; dg[j] = 0.f;
+      if (j < k && valid) {
+        ij[j] = idx[t * k + j];
+        ps[j] = (unsigned)ij[j] < (unsigned)E ? expf(row[ij[j]] - zmax) / zsum : 0.f;
+        dg[j] = dgate[t * k + j];
+        ssum += ps[j];
+        dot += dg[j] * gate[t * k + j];
+      }
+    }
+    // gradient w.r.t. the selected probabilities, then its inner product with p
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAX_K; ++j) {
+      if (j < k) {
+        if (renorm) dg[j] = (dg[j] - dot) / ssum;
+        s += dg[j] * ps[j];
+      }
+    }
+    if (!valid) continue;
+    const bool vec_ok = (E & 3) == 0;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int col0 = (v * G + g) * 4;
+      float out[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int col = col0 + c;
+        float dp = 0.f;
+#pragma unroll
+        for (int j = 0; j < MAX_K; ++j)
+          if (j < k && ij[j] == col) dp = dg[j];
+        const float p = col < E ? expf(z[v * 4 + c] - zmax) / zsum : 0.f;
+        out[c] = p * (dp - s);
+      }
+      float* dst = dlogits + t * E + col0;
+      if (vec_ok && col0 + 3 < E) {
+        *reinterpret_cast<float4*>(dst) = make_float4(out[0], out[1], out[2], out[3]);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (col0 + c < E) dst[c] = out[c];
+      }
+    }
+  }
+}
+
+static void route_shape(int E, int& G, int& NV) {
+  const int vecs = (E + 3) / 4;
+  G = 1;
+  while (G < vecs && G < 64) G <<= 1;
+  const int need = (vecs + G - 1) / G;
+  NV = need <= 1 ? 1 : (need <= 2 ? 2 : 4);
+}
+
+static int route_grid(int T, int G) {
+  const int tpb = (ROUTE_THREADS / 64) * (64 / G);
+  int grid = cdiv(T, tpb);
+  return grid < 1 ? 1 : (grid > 8192 ? 8192 : grid);
+}
+
+}  // namespace symi
+
+using namespace symi;
+
+extern "C" int symi_route(const symi_cfg* cfg, const float* logits, int32_t* idx, float* gate,
+                          int32_t* hist, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_route")) return rc;
+  SYMI_REQUIRE(hist && (cfg->T == 0 || (logits && idx && gate)), "symi_route", "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  const int E = cfg->E;
+  launch_fill_i32(hist, E, 0, st);
+  if (cfg->T > 0) {
+    int G, NV;
+    route_shape(E, G, NV);
+    const int grid = route_grid(cfg->T, G);
+    const size_t sh = (size_t)E * sizeof(int32_t);
+    if (NV == 1)
+      route_kernel<1><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm);
+    else if (NV == 2)
+      route_kernel<2><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm);
+    else
+      route_kernel<4><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm);
+  }
+  SYMI_LAUNCH_CHECK("symi_route");
+  return SYMI_OK;
+}
+
+extern "C" int symi_route_bwd(const symi_cfg* cfg, const float* logits, const int32_t* idx,
+                              const float* gate, const float* dgate, float* dlogits,
+                              void* stream) {
+  if (int rc = check_cfg(cfg, "symi_route_bwd")) return rc;
+  if (cfg->T == 0) return SYMI_OK;
+  SYMI_REQUIRE(logits && idx && gate && dgate && dlogits, "symi_route_bwd", "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  int G, NV;
+  route_shape(cfg->E, G, NV);
+  const int grid = route_grid(cfg->T, G);
+  if (NV == 1)
+    route_bwd_kernel<1><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm);
+  else if (NV == 2)
+    route_bwd_kernel<2><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm);
+  else
+    route_bwd_kernel<4><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm);
+  SYMI_LAUNCH_CHECK("symi_route_bwd");
+  return SYMI_OK;
+}

@@ -1,0 +1,184 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element, on the five workload recipes at sizes the oracle finishes in seconds (several
+tiles, ragged tails, empty groups), plus edge cases.  Integer outputs bit-exact; floats
+within 1e-5 (fp32 path, routing data), 2e-2 (bf16 path), 1e-6 (Adam state)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import symi_oracle as O
+from tests import harness as Hn
+from tests.util import TOL, check_close, relerr_elem
+
+pytestmark = pytest.mark.gpu
+
+
+def _small(name):
+    c = wl.get_config(name)
+    if name == "c1":
+        return c                                                     # full size
+    if name == "c2":
+        return wl.scaled(c, d=256, f=384, T=1500, iters=3)           # ragged rows, f = 3 tiles
+    if name == "c3":
+        return wl.scaled(c, d=512, f=1000, T=2100)                   # f not a tile multiple
+    if name == "c4":
+        return wl.scaled(c, d=192, f=352, T=1111, iters=3)           # top-6, 128 slots
+    if name == "c5":
+        return wl.scaled(c, d=256, f=136, T=3001)                    # top-8, 256 slots
+    raise KeyError(name)
+
+
+def check_iteration(st: Hn.State, X, logits, dY, hp_kw=None, check_float=True):
+    """One full iteration on the GPU, every stage compared with the oracle."""
+    c, cfg = st.c, st.cfg
+    hist_prev = st.hist_prev.cpu().numpy()
+    st.place_current()
+    st.forward(X, logits)
+    st.backward(dY, logits)
+    adam, hp = Hn.make_adam(**(hp_kw or {}))
+    master0, m0, v0 = Hn.npf(st.master), Hn.npf(st.m), Hn.npf(st.v)
+    W1s0, W2s0 = Hn.npf(st.W1s).copy(), Hn.npf(st.W2s).copy()
+    st.optimizer(adam)
+    Hn.sync()
+
+    Xn, zn, dYn = Hn.npf(X), Hn.npf(logits), Hn.npf(dY)
+    # ---- integers: bit exact
+    o_counts, o_place, o_first = O.place(hist_prev, c.S_tot)
+    assert (st.counts.cpu().numpy() == o_counts).all()
+    assert (st.placement.cpu().numpy() == o_place).all()
+    assert (st.first_slot.cpu().numpy() == o_first).all()
+    o_idx, o_gate, o_hist = O.route(zn, c.k, bool(cfg.renorm))
+    assert (st.idx.cpu().numpy() == o_idx).all()
+    assert (st.hist.cpu().numpy() == o_hist).all()
+    assert o_hist.sum() == c.A
+    o_roa, o_aor, o_off = O.dispatch(o_idx, o_counts, o_first)
+    assert (st.row_of_assign.cpu().numpy() == o_roa).all()
+    assert (st.assign_of_row.cpu().numpy() == o_aor).all()
+    assert (st.slot_offsets.cpu().numpy() == o_off).all()
+    n_counts, n_place, n_first = O.place(o_hist, c.S_tot)
+    assert (st.counts_next.cpu().numpy() == n_counts).all()
+    assert (st.placement_next.cpu().numpy() == n_place).all()
+    assert (st.first_slot_next.cpu().numpy() == n_first).all()
+    # the gather is a copy: bit exact
+    if c.A:
+        assert torch.equal(st.Xp, X[(st.assign_of_row // c.k).long()])
+    if not check_float:
+        return
+    # ---- floats
+    log = {}
+    assert relerr_elem(Hn.npf(st.gate), o_gate) <= TOL["f32"]
+    W1n, W2n = Hn.npf(st.W1c), Hn.npf(st.W2c)
+    Y = O.moe_forward(Xn, o_idx, o_gate, W1n, W2n)
+    check_close("Y", Hn.npf(st.Y), Y, c.dtype, log=log)
+    dX, dW1, dW2, dgate = O.moe_backward(Xn, o_idx, o_gate, W1n, W2n, dYn)
+    dlog = O.route_backward(zn, o_idx, o_gate, dgate, bool(cfg.renorm))
+    check_close("dX", Hn.npf(st.dX), dX, c.dtype, log=log)
+    check_close("dW1", Hn.npf(st.dW1), dW1, c.dtype, group_axis=0, log=log)   # per class
+    check_close("dW2", Hn.npf(st.dW2), dW2, c.dtype, group_axis=0, log=log)
+    check_close("dgate", Hn.npf(st.dgate), dgate, c.dtype, log=log)
+    check_close("dlogits", Hn.npf(st.dlogits), dlog, c.dtype, log=log)
+    print("[err] " + " ".join(f"{k}:max={v['max']:.2e},l2={v['l2']:.2e},elem={v['elem']:.2e}"
+                              for k, v in log.items()), flush=True)
+    # the router backward on its own (fed the same dgate) is an fp32 computation
+    dlog_iso = O.route_backward(zn, o_idx, Hn.npf(st.gate), Hn.npf(st.dgate), bool(cfg.renorm))
+    assert relerr_elem(Hn.npf(st.dlogits), dlog_iso) <= TOL["f32"]
+    # classes without rows have exactly zero gradient
+    for e in np.nonzero(o_hist == 0)[0]:
+        assert not st.dW1[e].any() and not st.dW2[e].any()
+    # ---- Adam on the shard, fed the GPU's own gradients (stage isolated)
+    W1s_o, W2s_o = W1s0.copy(), W2s0.copy()
+    w2, m2, v2 = O.adam_to_replicas(Hn.npf(st.dW1), Hn.npf(st.dW2), master0, m0, v0, n_place, c.N,
+                                    cfg.shard, hp, c.dtype == "bf16", W1s_o, W2s_o)
+    assert relerr_elem(Hn.npf(st.master), w2) <= TOL["adam"]
+    assert relerr_elem(Hn.npf(st.m), m2) <= TOL["adam"]
+    assert relerr_elem(Hn.npf(st.v), v2) <= TOL["adam"]
+    # slots: exactly the rounding of the GPU's own fresh master weights on the shard's
+    # range of every slot of the NEXT placement, untouched elsewhere
+    per = c.P_e // c.N
+    lo = cfg.shard * per
+    slots = torch.cat([st.W1s.reshape(c.S_tot, -1), st.W2s.reshape(c.S_tot, -1)], 1)
+    want = st.master[st.placement_next.long()].to(st.W1s.dtype)
+    assert torch.equal(slots[:, lo:lo + per], want)
+    before = np.concatenate([W1s0.reshape(c.S_tot, -1), W2s0.reshape(c.S_tot, -1)], 1)
+    sl = Hn.npf(slots)
+    assert (sl[:, :lo] == before[:, :lo]).all() and (sl[:, lo + per:] == before[:, lo + per:]).all()
+    # and close to the oracle's slots (1 bf16 ulp where fp32 rounding straddles a tie)
+    so = np.concatenate([W1s_o.reshape(c.S_tot, -1), W2s_o.reshape(c.S_tot, -1)], 1)
+    if c.dtype == "bf16":
+        assert (np.abs(sl - so) <= 2.0 ** -7 * np.abs(so) + 1e-30).all()
+    else:
+        assert relerr_elem(sl, so) <= TOL["adam"]
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_config_parity(name):
+    c = _small(name)
+    print(f"[parity] {name}: {c}", flush=True)
+    st = Hn.State(c, shard=min(1, c.N - 1))
+    for it in range(min(c.iters, 3)):
+        X, logits, dY = Hn.draw_inputs(c, it)
+        check_iteration(st, X, logits, dY, hp_kw=dict(step=it + 1))
+        st.hist_prev.copy_(st.hist)     # next iteration mimics this one's popularity
+
+
+def test_placement_invariance_of_the_layer():
+    """Replication changes where a row is processed, not the result: Y and the class
+    gradients under a skewed placement equal those under the uniform one (bit for bit in
+    the forward, because every row sees the same weights and reduction order)."""
+    c = wl.scaled(wl.get_config("c2"), d=128, f=256, T=700, E=8, S_tot=24)
+    X, logits, dY = Hn.draw_inputs(c, 0)
+    outs = []
+    for pop in ([0] * 8, [1000, 1, 1, 1, 1, 1, 1, 1], [0, 0, 0, 0, 0, 0, 0, 999]):
+        st = Hn.State(c)
+        st.hist_prev.copy_(torch.tensor(pop, dtype=torch.int32))
+        st.place_current()
+        st.forward(X, logits)
+        st.backward(dY, logits)
+        Hn.sync()
+        outs.append((st.Y.clone(), st.dX.clone(), st.dW1.clone(), st.dW2.clone(),
+                     st.counts.cpu().tolist()))
+    assert outs[0][4] != outs[1][4] != outs[2][4]
+    for o in outs[1:]:
+        assert torch.equal(o[0], outs[0][0])
+        assert torch.equal(o[1], outs[0][1])
+        assert relerr_elem(Hn.npf(o[2]), Hn.npf(outs[0][2])) < 1e-5
+        assert relerr_elem(Hn.npf(o[3]), Hn.npf(outs[0][3])) < 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_edge_cases(dtype):
+    base = wl.scaled(wl.get_config("c1"), dtype=dtype)
+    cases = [
+        wl.scaled(base, T=1, E=1, k=1, S_tot=1, N=1, d=8, f=8),            # smallest legal shape
+        wl.scaled(base, T=5, E=4, k=4, S_tot=4, N=2, d=16, f=24),          # k = E, one slot per class
+        wl.scaled(base, T=130, E=3, k=1, S_tot=64, N=3, d=40, f=72),       # many more slots than rows/classes
+        wl.scaled(base, T=257, E=24, k=2, S_tot=24, N=1, d=72, f=200),     # E not a power of two
+        wl.scaled(base, T=0, E=8, k=2, S_tot=16, N=4, d=128, f=256),       # empty batch
+        wl.scaled(base, T=300, E=130, k=5, S_tot=257, N=2, d=64, f=64, router_matmul=False,
+                  bias="zipf", zipf_s=1.2),                                # E > 128, S_tot > 256
+    ]
+    for c in cases:
+        print(f"[edge] {c}", flush=True)
+        st = Hn.State(c, shard=c.N - 1)
+        X, logits, dY = Hn.draw_inputs(c, 0)
+        check_iteration(st, X, logits, dY)
+
+
+def test_tied_logits_and_renorm_off():
+    c = wl.scaled(wl.get_config("c1"), T=512, E=64, k=6, S_tot=80, router_matmul=False)
+    st = Hn.State(c, renorm=0)
+    X, logits, dY = Hn.draw_inputs(c, 0)
+    logits = (logits * 2).round() / 2          # many exact ties inside every row
+    logits[::5] = 0.0                          # fully tied rows
+    check_iteration(st, X, logits.contiguous(), dY)
+
+
+def test_adam_weight_decay_grad_scale_and_later_steps():
+    c = wl.scaled(wl.get_config("c2"), d=64, f=96, T=400, E=8, S_tot=12, N=4)
+    st = Hn.State(c, shard=3)
+    for it in range(3):
+        X, logits, dY = Hn.draw_inputs(c, it)
+        check_iteration(st, X, logits, dY, hp_kw=dict(step=it + 1, weight_decay=0.05,
+                                                      grad_scale=0.125, lr=3e-3))
+        st.hist_prev.copy_(st.hist)
