@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the Symi MoE hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input already
+resident in HBM: route -> dispatch -> expert forward -> combine -> combine backward ->
+expert backward -> dispatch backward -> route backward -> place (next placement) ->
+Adam on this GPU's 1/N shard + write into the next placement's replica slots.  The
+default workload is config c2 of the benchmark spec (bf16, E=64, top-2, d=1024, f=4096,
+T=8192, 96 slots, N=8, Zipf-1.2 popularity whose ranking is reshuffled every iteration);
+steps cycle through its 10 iterations.
+
+Prints ONE JSON line: whole-job tokens/s, the roofline of the dominant kernel (from HIP
+events recorded around every launch inside the timed region) and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TF = 2500.0     # dense bf16 MFMA
+FP32_VEC_PEAK_TF = 157.3       # fp32 vector FMA
+
+
+def kernel_work(c, w, nonempty_slots):
+    """Algorithmic (flops, bytes) of one launch of each kernel for workload c."""
+    T, E, k, d, f, S, N = c.T, c.E, c.k, c.d, c.f, c.S_tot, c.N
+    A = T * k
+    Sn = nonempty_slots
+    nblk = (A + 1023) // 1024
+    per = 3 * d * f // N
+    return {
+        "route": (0, T * (4 * E + 8 * k) + 4 * E),
+        "route_bwd": (0, T * (8 * E + 12 * k)),
+        "chunk_count": (0, 4 * A + 4 * nblk * E),
+        "chunk_scan": (0, 8 * nblk * E),
+        "chunk_rank": (0, 12 * A + 4 * nblk * E),
+        "gather_rows": (0, T * d * w + A * d * w + 4 * A),
+        "gemm_fwd1": (2 * A * d * 2 * f, Sn * 2 * f * d * w + A * d * w + A * 3 * f * w),
+        "gemm_fwd2": (2 * A * f * d, Sn * d * f * w + A * f * w + A * d * w),
+        "gemm_bwd_dh": (2 * A * d * f, Sn * d * f * w + A * d * w + A * 4 * f * w),
+        "gemm_bwd_dx": (2 * A * 2 * f * d, Sn * 2 * f * d * w + A * 2 * f * w + A * d * w),
+        "gemm_wgrad2": (2 * A * d * f, A * d * w + A * f * w + E * d * f * 4),
+        "gemm_wgrad1": (2 * A * 2 * f * d, A * 2 * f * w + A * d * w + E * 2 * f * d * 4),
+        "combine": (0, A * d * w + T * d * w + 8 * A),
+        "combine_bwd": (0, T * d * w + 2 * A * d * w + 12 * A),
+        "dispatch_bwd": (0, A * d * w + T * d * w + 4 * A),
+        "adam_to_replicas": (0, E * per * 28 + S * per * w),
+    }
+
+
+def run_gpu(args):
+    import torch
+    import paper_2504_19925_amd as symi
+    import workloads as wl
+    from tests import harness as Hn
+
+    c = wl.get_config(args.config)
+    torch.cuda.set_device(0)
+    st = Hn.State(c, shard=0)
+    iters = max(c.iters, 1)
+    inputs = [Hn.draw_inputs(c, it) for it in range(iters)]
+    adam, _ = Hn.make_adam()
+    st.place_current()            # placement of iteration 0 (uniform) + slot weights
+    Hn.sync()
+
+    def step(i):
+        X, logits, dY = inputs[i % iters]
+        st.forward(X, logits)
+        st.backward(dY, logits)
+        st.optimizer(adam)
+        # the placement computed in this step is the one the next step dispatches with
+        st.counts, st.counts_next = st.counts_next, st.counts
+        st.first_slot, st.first_slot_next = st.first_slot_next, st.first_slot
+        st.placement, st.placement_next = st.placement_next, st.placement
+
+    fwd_bwd_ms = None
+    for i in range(args.warmup):
+        step(i)
+    Hn.sync()
+    symi.symi_timing_reset()
+    symi.symi_timing_enable(True)
+    Hn.sync()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    Hn.sync()
+    t1 = time.perf_counter()
+    symi.symi_timing_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # per-kernel durations of the timed region
+    w = 2 if c.dtype == "bf16" else 4
+    times = {}
+    for kid in range(symi.symi_kernel_count()):
+        ms, n = symi.symi_timing_read(kid)
+        if n:
+            times[symi.symi_kernel_name(kid)] = (ms / n, n)
+    symi.symi_timing_reset()
+
+    # slots that actually hold rows (their weights are the ones a step must read)
+    nonempty = []
+    for i in range(iters):
+        step(args.warmup + args.steps + i)
+        Hn.sync()
+        so = st.slot_offsets.cpu()
+        nonempty.append(int((so[1:] > so[:-1]).sum()))
+    mean_nonempty = sum(nonempty) / len(nonempty)
+
+    work = kernel_work(c, w, mean_nonempty)
+    peak_tf = MFMA_BF16_PEAK_TF if c.dtype == "bf16" else FP32_VEC_PEAK_TF
+    kernels = {}
+    for name, (avg_ms, n) in times.items():
+        entry = {"avg_us": round(avg_ms * 1e3, 2), "launches_per_step": round(n / args.steps, 2)}
+        if name in work:
+            fl, by = work[name]
+            entry["GB/s"] = round(by / (avg_ms * 1e-3) / 1e9, 1)
+            if fl:
+                entry["TFLOP/s"] = round(fl / (avg_ms * 1e-3) / 1e12, 1)
+        kernels[name] = entry
+    gpu_ms = sum(avg * n for avg, n in times.values()) / args.steps
+    fb = [k_ for k_ in times if k_ not in ("place", "adam_to_replicas")]
+    fwd_bwd_ms = sum(times[k_][0] * times[k_][1] for k_ in fb) / args.steps
+
+    dom = max((k_ for k_ in times if k_ in work), key=lambda k_: times[k_][0] * times[k_][1])
+    fl, by = work[dom]
+    avg_s = times[dom][0] * 1e-3
+    t_hbm, t_mfma = by / (HBM_PEAK_GBS * 1e9), fl / (peak_tf * 1e12)
+    if t_mfma > t_hbm:
+        bound = "mfma" if c.dtype == "bf16" else "alu"
+        roof = {"bound": bound, "achieved": round(fl / avg_s / 1e12, 2), "peak": peak_tf,
+                "unit": "TFLOP/s", "frac": round(fl / avg_s / 1e12 / peak_tf, 4)}
+    else:
+        roof = {"bound": "hbm", "achieved": round(by / avg_s / 1e9, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(by / avg_s / 1e9 / HBM_PEAK_GBS, 4)}
+    roof.update({"kernel": dom, "avg_us": round(avg_s * 1e6, 2), "traffic": None,
+                 "algorithmic_bytes": by, "algorithmic_flops": fl})
+
+    out = {
+        "metric": "MoE layer fwd+bwd tokens/s; grouped-GEMM MFMA %; Adam+scatter HBM GB/s",
+        "value": round(c.T / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": c.dtype, "data": "synthetic",
+        "config": {"workload": f"{c.name}: {c.dtype} E={c.E} top-{c.k} d={c.d} f={c.f} T={c.T} "
+                               f"S_tot={c.S_tot} N={c.N} (1 shard of {c.N}), {iters} iteration(s) cycled",
+                   "step": "route+dispatch+expert_fwd+combine+backward+place+adam_to_replicas"},
+        "roofline": roof,
+        "fwd_bwd_tokens_per_s": round(c.T / (fwd_bwd_ms * 1e-3), 1),
+        "gpu_kernel_ms_per_step": round(gpu_ms, 4),
+        "nonempty_slots_mean": round(mean_nonempty, 2),
+        "kernels": kernels,
+    }
+    return out, c
+
+
+def cpu_baseline(c, seconds_hint=20.0):
+    """The oracle as it stands, timed on a bounded sample of the same workload."""
+    import numpy as np
+    import workloads as wl
+    from oracle import symi_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+
+    Ts = min(c.T, 1024)                      # tokens of the sample (all E classes, full d, f)
+    Es = min(c.E, 8)                         # classes whose shard the sampled Adam step covers
+    X = wl.make_tokens(c, 0, "cpu")[:Ts].float().numpy()
+    z = wl.make_logits(c, 0, "cpu")[:Ts].numpy() if not c.router_matmul else \
+        wl.make_logits(c, 0, "cpu", tokens=wl.make_tokens(c, 0, "cpu"))[:Ts].numpy()
+    dY = wl.make_upstream_grad(c, 0, "cpu")[:Ts].float().numpy()
+    W1, W2 = wl.make_class_weights(c, "cpu")
+    W1, W2 = W1.float().numpy(), W2.float().numpy()
+
+    t0 = time.perf_counter()
+    idx, gate, hist = O.route(z, c.k, True)
+    counts, placement, first = O.place(np.zeros(c.E, dtype=np.int64), c.S_tot)
+    O.dispatch(idx, counts, first)
+    O.moe_forward(X, idx, gate, W1, W2)
+    dX, dW1, dW2, dgate = O.moe_backward(X, idx, gate, W1, W2, dY)
+    O.route_backward(z, idx, gate, dgate, True)
+    n_counts, n_place, n_first = O.place(hist, c.S_tot)
+    t_layer = time.perf_counter() - t0
+
+    per = c.P_e // c.N
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, grad_scale=1.0, step=1)
+    sub_place = np.array([e for e in n_place if e < Es], dtype=np.int32)
+    W1s = np.zeros((len(sub_place),) + W1.shape[1:], np.float32)
+    W2s = np.zeros((len(sub_place),) + W2.shape[1:], np.float32)
+    flat = np.concatenate([W1[:Es].reshape(Es, -1), W2[:Es].reshape(Es, -1)], 1)[:, :per]
+    t0 = time.perf_counter()
+    O.adam_to_replicas(dW1[:Es], dW2[:Es], flat, np.zeros_like(flat), np.zeros_like(flat), sub_place,
+                       c.N, 0, hp, c.dtype == "bf16", W1s, W2s)
+    t_adam = time.perf_counter() - t0
+
+    est_step = t_layer * (c.T / Ts) + t_adam * (c.E / Es)
+    return {"value": round(c.T / est_step, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"layer fwd+bwd+routing on the first {Ts} of {c.T} tokens ({t_layer:.2f} s), "
+                      f"Adam+replica write on {Es} of {c.E} classes' shard ({t_adam:.2f} s); "
+                      f"scaled linearly to one full step ({est_step:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's share of the path; --gpus must be 1 "
+              "(no collectives are part of it)", file=sys.stderr)
+        sys.exit(2)
+    out, c = run_gpu(args)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(c)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -149,6 +149,20 @@ int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp, const float*
                           const int32_t* first_slot_next, void* W1_slots, void* W2_slots,
                           void* stream);
 
+/* Measurement aid (not part of the method): while enabled, every kernel the library
+ * launches is bracketed by two HIP events recorded on the launch stream, so that a
+ * benchmark can read per-kernel durations of its own timed region.  Enabling it makes
+ * calls create events (a host-side allocation); it is off by default.  Kernel ids run
+ * from 0 to symi_kernel_count()-1 and have the names symi_kernel_name() returns.
+ * symi_timing_read waits for the recorded events of that kernel and returns the summed
+ * duration in milliseconds and the number of launches since the last reset.  Host
+ * pointers; not thread safe. */
+int symi_timing_enable(int on);
+int symi_timing_reset(void);
+int symi_timing_read(int kernel_id, double* total_ms, int* launches);
+int symi_kernel_count(void);
+const char* symi_kernel_name(int kernel_id);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,5 +23,10 @@ from .binding import (  # noqa: F401
     symi_combine,
     symi_combine_bwd,
     symi_adam_to_replicas,
+    symi_timing_enable,
+    symi_timing_reset,
+    symi_timing_read,
+    symi_kernel_count,
+    symi_kernel_name,
     EXPORTS,
 )

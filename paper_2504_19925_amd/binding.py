@@ -17,6 +17,8 @@ EXPORTS = [
     "symi_validate", "symi_workspace_bytes", "symi_last_error", "symi_route", "symi_route_bwd",
     "symi_place", "symi_place_host", "symi_dispatch", "symi_dispatch_bwd", "symi_expert_fwd",
     "symi_expert_bwd", "symi_combine", "symi_combine_bwd", "symi_adam_to_replicas",
+    "symi_timing_enable", "symi_timing_reset", "symi_timing_read", "symi_kernel_count",
+    "symi_kernel_name",
 ]
 
 
@@ -83,6 +85,13 @@ def lib():
         L.symi_workspace_bytes.restype = ctypes.c_size_t
         L.symi_last_error.argtypes = []
         L.symi_last_error.restype = ctypes.c_char_p
+        L.symi_timing_enable.argtypes = [ctypes.c_int]
+        L.symi_timing_reset.argtypes = []
+        L.symi_timing_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                       ctypes.POINTER(ctypes.c_int)]
+        L.symi_kernel_count.argtypes = []
+        L.symi_kernel_name.argtypes = [ctypes.c_int]
+        L.symi_kernel_name.restype = ctypes.c_char_p
         _LIB = L
     return _LIB
 
@@ -121,6 +130,30 @@ def _stream():
 
 
 I32, F32 = torch.int32, torch.float32
+
+
+def symi_timing_enable(on):
+    _check(lib().symi_timing_enable(int(bool(on))), "symi_timing_enable")
+
+
+def symi_timing_reset():
+    _check(lib().symi_timing_reset(), "symi_timing_reset")
+
+
+def symi_timing_read(kernel_id):
+    """(total milliseconds, launches) of one kernel id since the last reset."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int(0)
+    _check(lib().symi_timing_read(int(kernel_id), ctypes.byref(ms), ctypes.byref(n)),
+           "symi_timing_read")
+    return ms.value, n.value
+
+
+def symi_kernel_count():
+    return lib().symi_kernel_count()
+
+
+def symi_kernel_name(kernel_id):
+    return lib().symi_kernel_name(int(kernel_id)).decode()
 
 
 def symi_validate(cfg):

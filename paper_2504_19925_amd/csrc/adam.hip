@@ -109,12 +109,13 @@ extern "C" int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp,
   if (gx > 4096) gx = 4096;
   if (gx < 1) gx = 1;
   dim3 grid((unsigned)gx, (unsigned)cfg->E);
+  hipStream_t st = as_stream(stream);
   if (cfg->dtype == SYMI_BF16)
-    adam_to_replicas_kernel<true><<<grid, 256, 0, as_stream(stream)>>>(
-        dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s);
+    SYMI_TIMED(K_ADAM, st, (adam_to_replicas_kernel<true><<<grid, 256, 0, st>>>(
+        dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s)));
   else
-    adam_to_replicas_kernel<false><<<grid, 256, 0, as_stream(stream)>>>(
-        dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s);
+    SYMI_TIMED(K_ADAM, st, (adam_to_replicas_kernel<false><<<grid, 256, 0, st>>>(
+        dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s)));
   SYMI_LAUNCH_CHECK("symi_adam_to_replicas");
   return SYMI_OK;
 }

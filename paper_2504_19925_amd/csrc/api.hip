@@ -2,6 +2,8 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <vector>
+
 #include "common.h"
 
 namespace symi {
@@ -62,9 +64,79 @@ WsLayout ws_layout(const symi_cfg* c) {
   return L;
 }
 
+// ---- optional per-kernel event timing (off by default; used by the benchmark)
+bool g_timing = false;
+struct TimedLaunch { int kid; hipEvent_t a, b; };
+static std::vector<TimedLaunch> g_launches;
+static hipEvent_t g_open[K_COUNT];
+static const char* const g_names[K_COUNT] = {
+    "fill_i32", "route", "route_bwd", "place", "chunk_count", "chunk_scan", "chunk_rank",
+    "gather_rows", "tile_map", "gemm_fwd1", "gemm_fwd2", "gemm_bwd_dh", "gemm_bwd_dx",
+    "gemm_wgrad2", "gemm_wgrad1", "combine", "combine_bwd", "dispatch_bwd", "adam_to_replicas"};
+
+void timing_begin(int kid, hipStream_t st) {
+  hipEvent_t e;
+  if (hipEventCreate(&e) != hipSuccess) return;
+  (void)hipEventRecord(e, st);
+  g_open[kid] = e;
+}
+void timing_end(int kid, hipStream_t st) {
+  hipEvent_t e;
+  if (!g_open[kid] || hipEventCreate(&e) != hipSuccess) return;
+  (void)hipEventRecord(e, st);
+  g_launches.push_back({kid, g_open[kid], e});
+  g_open[kid] = nullptr;
+}
+
 }  // namespace symi
 
 extern "C" {
+
+int symi_timing_enable(int on) {
+  symi::g_timing = on != 0;
+  return SYMI_OK;
+}
+
+int symi_timing_reset(void) {
+  for (auto& l : symi::g_launches) {
+    (void)hipEventDestroy(l.a);
+    (void)hipEventDestroy(l.b);
+  }
+  symi::g_launches.clear();
+  return SYMI_OK;
+}
+
+int symi_timing_read(int kernel_id, double* total_ms, int* launches) {
+  if (kernel_id < 0 || kernel_id >= symi::K_COUNT || !total_ms || !launches) {
+    symi::set_error("symi_timing_read: bad argument");
+    return SYMI_EINVAL;
+  }
+  double tot = 0.0;
+  int n = 0;
+  for (auto& l : symi::g_launches) {
+    if (l.kid != kernel_id) continue;
+    if (hipEventSynchronize(l.b) != hipSuccess) {
+      symi::set_error("symi_timing_read: hipEventSynchronize failed");
+      return SYMI_EHIP;
+    }
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, l.a, l.b) != hipSuccess) {
+      symi::set_error("symi_timing_read: hipEventElapsedTime failed");
+      return SYMI_EHIP;
+    }
+    tot += ms;
+    ++n;
+  }
+  *total_ms = tot;
+  *launches = n;
+  return SYMI_OK;
+}
+
+int symi_kernel_count(void) { return symi::K_COUNT; }
+
+const char* symi_kernel_name(int kernel_id) {
+  return kernel_id >= 0 && kernel_id < symi::K_COUNT ? symi::g_names[kernel_id] : "";
+}
 
 int symi_validate(const symi_cfg* cfg) { return symi::check_cfg(cfg, "symi_validate"); }
 

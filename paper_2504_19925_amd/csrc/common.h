@@ -12,6 +12,24 @@ void set_error(const char* fmt, ...);
 int check_cfg(const symi_cfg* cfg, const char* who);
 void launch_fill_i32(int32_t* p, int n, int32_t val, hipStream_t st);
 
+// Kernel ids for the optional event timing (symi_timing_*).
+enum KernelId {
+  K_FILL = 0, K_ROUTE, K_ROUTE_BWD, K_PLACE, K_CHUNK_COUNT, K_CHUNK_SCAN, K_CHUNK_RANK, K_GATHER,
+  K_TILE_MAP, K_GEMM_FWD1, K_GEMM_FWD2, K_GEMM_BWD_DH, K_GEMM_BWD_DX, K_GEMM_WGRAD2, K_GEMM_WGRAD1,
+  K_COMBINE, K_COMBINE_BWD, K_DISPATCH_BWD, K_ADAM, K_COUNT
+};
+extern bool g_timing;
+void timing_begin(int kid, hipStream_t st);
+void timing_end(int kid, hipStream_t st);
+
+// Brackets one kernel launch with events when timing is on; otherwise just launches.
+#define SYMI_TIMED(kid, st, launch)            \
+  do {                                         \
+    if (symi::g_timing) symi::timing_begin(kid, st); \
+    launch;                                    \
+    if (symi::g_timing) symi::timing_end(kid, st);   \
+  } while (0)
+
 #define SYMI_REQUIRE(cond, who, msg)                      \
   do {                                                    \
     if (!(cond)) {                                        \

@@ -263,17 +263,17 @@ extern "C" int symi_dispatch(const symi_cfg* cfg, const void* X, const int32_t* 
   int32_t* blk = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.blk_counts);
   const int nblk = cdiv(A, DISPATCH_CHUNK);
   if (nblk > 0)
-    chunk_count_kernel<<<nblk, DT, E * sizeof(int32_t), st>>>(idx, A, E, blk);
-  chunk_scan_kernel<<<E, DT, 0, st>>>(blk, nblk, E, cfg->S_tot, A, hist, counts, first_slot,
-                                      slot_offsets);
+    SYMI_TIMED(K_CHUNK_COUNT, st, (chunk_count_kernel<<<nblk, DT, E * sizeof(int32_t), st>>>(idx, A, E, blk)));
+  SYMI_TIMED(K_CHUNK_SCAN, st, (chunk_scan_kernel<<<E, DT, 0, st>>>(blk, nblk, E, cfg->S_tot, A, hist, counts,
+                                                                    first_slot, slot_offsets)));
   if (nblk > 0) {
-    chunk_rank_kernel<<<nblk, DT, (size_t)(1 + DT / 64) * E * sizeof(int32_t), st>>>(
-        idx, A, E, blk, row_of_assign, assign_of_row);
+    SYMI_TIMED(K_CHUNK_RANK, st, (chunk_rank_kernel<<<nblk, DT, (size_t)(1 + DT / 64) * E * sizeof(int32_t), st>>>(
+        idx, A, E, blk, row_of_assign, assign_of_row)));
     const int w = cfg->dtype == SYMI_BF16 ? 2 : 4;
     const int vpr = cfg->d * w / 16;
     const long long nvec = (long long)A * vpr;
-    gather_rows_kernel<<<grid_for(nvec, 256 * 4), 256, 0, st>>>(
-        static_cast<const uint4*>(X), static_cast<uint4*>(Xp), assign_of_row, cfg->k, nvec, vpr);
+    SYMI_TIMED(K_GATHER, st, (gather_rows_kernel<<<grid_for(nvec, 256 * 4), 256, 0, st>>>(
+        static_cast<const uint4*>(X), static_cast<uint4*>(Xp), assign_of_row, cfg->k, nvec, vpr)));
   }
   SYMI_LAUNCH_CHECK("symi_dispatch");
   return SYMI_OK;
@@ -287,12 +287,12 @@ extern "C" int symi_dispatch_bwd(const symi_cfg* cfg, const void* dXp, const int
   hipStream_t st = as_stream(stream);
   if (cfg->dtype == SYMI_BF16) {
     const int ppr = cfg->d / 8;
-    combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
-        dXp, row_of_assign, nullptr, dX, cfg->T, cfg->k, ppr);
+    SYMI_TIMED(K_DISPATCH_BWD, st, (combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+        dXp, row_of_assign, nullptr, dX, cfg->T, cfg->k, ppr)));
   } else {
     const int ppr = cfg->d / 4;
-    combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
-        dXp, row_of_assign, nullptr, dX, cfg->T, cfg->k, ppr);
+    SYMI_TIMED(K_DISPATCH_BWD, st, (combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+        dXp, row_of_assign, nullptr, dX, cfg->T, cfg->k, ppr)));
   }
   SYMI_LAUNCH_CHECK("symi_dispatch_bwd");
   return SYMI_OK;
@@ -306,12 +306,12 @@ extern "C" int symi_combine(const symi_cfg* cfg, const void* Yp, const int32_t* 
   hipStream_t st = as_stream(stream);
   if (cfg->dtype == SYMI_BF16) {
     const int ppr = cfg->d / 8;
-    combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
-        Yp, row_of_assign, gate, Y, cfg->T, cfg->k, ppr);
+    SYMI_TIMED(K_COMBINE, st, (combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+        Yp, row_of_assign, gate, Y, cfg->T, cfg->k, ppr)));
   } else {
     const int ppr = cfg->d / 4;
-    combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
-        Yp, row_of_assign, gate, Y, cfg->T, cfg->k, ppr);
+    SYMI_TIMED(K_COMBINE, st, (combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+        Yp, row_of_assign, gate, Y, cfg->T, cfg->k, ppr)));
   }
   SYMI_LAUNCH_CHECK("symi_combine");
   return SYMI_OK;
@@ -325,11 +325,11 @@ extern "C" int symi_combine_bwd(const symi_cfg* cfg, const void* dY, const void*
   SYMI_REQUIRE(dY && Yp && row_of_assign && gate && dYp && dgate, "symi_combine_bwd", "NULL pointer");
   hipStream_t st = as_stream(stream);
   if (cfg->dtype == SYMI_BF16)
-    combine_bwd_kernel<true><<<grid_for(cfg->T, 4), 256, 0, st>>>(dY, Yp, row_of_assign, gate, dYp,
-                                                                 dgate, cfg->T, cfg->k, cfg->d / 8);
+    SYMI_TIMED(K_COMBINE_BWD, st, (combine_bwd_kernel<true><<<grid_for(cfg->T, 4), 256, 0, st>>>(
+        dY, Yp, row_of_assign, gate, dYp, dgate, cfg->T, cfg->k, cfg->d / 8)));
   else
-    combine_bwd_kernel<false><<<grid_for(cfg->T, 4), 256, 0, st>>>(dY, Yp, row_of_assign, gate, dYp,
-                                                                  dgate, cfg->T, cfg->k, cfg->d / 4);
+    SYMI_TIMED(K_COMBINE_BWD, st, (combine_bwd_kernel<false><<<grid_for(cfg->T, 4), 256, 0, st>>>(
+        dY, Yp, row_of_assign, gate, dYp, dgate, cfg->T, cfg->k, cfg->d / 4)));
   SYMI_LAUNCH_CHECK("symi_combine_bwd");
   return SYMI_OK;
 }

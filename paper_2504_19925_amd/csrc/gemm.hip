@@ -468,11 +468,11 @@ static void launch_gemm(const symi_cfg* cfg, const GemmParams& p, int n_cols, in
   if (cfg->dtype == SYMI_BF16) {
     const int bn = MODE == FWD1 ? BN / 2 : BN;
     dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? max_mtiles : cdiv(p.M, BM), MODE <= BWD_DX ? 1 : cfg->E);
-    gemm_bf16_kernel<MODE><<<grid, GT, 0, st>>>(p);
+    SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_bf16_kernel<MODE><<<grid, GT, 0, st>>>(p)));
   } else {
     const int bn = MODE == FWD1 ? FB / 2 : FB;
     dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 2 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : cfg->E);
-    gemm_f32_kernel<MODE><<<grid, 256, 0, st>>>(p);
+    SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_f32_kernel<MODE><<<grid, 256, 0, st>>>(p)));
   }
 }
 
@@ -492,7 +492,7 @@ extern "C" int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_
   const WsLayout L = ws_layout(cfg);
   int32_t* map = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.tile_map);
   const int max_mtiles = (int)(A / GEMM_BM) + cfg->S_tot;
-  tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, cfg->S_tot, map);
+  SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, cfg->S_tot, map)));
 
   GemmParams p = {};
   p.tile_map = map;
@@ -535,7 +535,7 @@ extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void*
   p.d = cfg->d;
   p.f = cfg->f;
   if (A > 0) {
-    tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, cfg->S_tot, map);
+    SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, cfg->S_tot, map)));
     // dh = dYp W2, then du, dv
     p.A = dYp; p.B = W2_slots; p.C = dUV; p.UV = UV;
     p.b_group_stride = (long long)cfg->d * cfg->f;

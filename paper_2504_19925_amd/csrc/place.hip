@@ -158,8 +158,9 @@ extern "C" int symi_place(const symi_cfg* cfg, const int32_t* popularity, int32_
                           int32_t* placement, int32_t* first_slot, void* stream) {
   if (int rc = check_cfg(cfg, "symi_place")) return rc;
   SYMI_REQUIRE(popularity && counts && placement && first_slot, "symi_place", "NULL pointer");
-  place_kernel<<<1, 64, 0, as_stream(stream)>>>(popularity, counts, placement, first_slot, cfg->E,
-                                                cfg->S_tot);
+  hipStream_t st = as_stream(stream);
+  SYMI_TIMED(K_PLACE, st, (place_kernel<<<1, 64, 0, st>>>(popularity, counts, placement, first_slot,
+                                                        cfg->E, cfg->S_tot)));
   SYMI_LAUNCH_CHECK("symi_place");
   return SYMI_OK;
 }

@@ -24,7 +24,7 @@ __global__ void fill_i32_kernel(int32_t* p, int n, int32_t val) {
 }
 
 void launch_fill_i32(int32_t* p, int n, int32_t val, hipStream_t st) {
-  if (n > 0) fill_i32_kernel<<<cdiv(n, 256), 256, 0, st>>>(p, n, val);
+  if (n > 0) SYMI_TIMED(K_FILL, st, (fill_i32_kernel<<<cdiv(n, 256), 256, 0, st>>>(p, n, val)));
 }
 
 template <int NV>
@@ -230,11 +230,11 @@ extern "C" int symi_route(const symi_cfg* cfg, const float* logits, int32_t* idx
     const int grid = route_grid(cfg->T, G);
     const size_t sh = (size_t)E * sizeof(int32_t);
     if (NV == 1)
-      route_kernel<1><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm);
+      SYMI_TIMED(K_ROUTE, st, (route_kernel<1><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
     else if (NV == 2)
-      route_kernel<2><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm);
+      SYMI_TIMED(K_ROUTE, st, (route_kernel<2><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
     else
-      route_kernel<4><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm);
+      SYMI_TIMED(K_ROUTE, st, (route_kernel<4><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
   }
   SYMI_LAUNCH_CHECK("symi_route");
   return SYMI_OK;
@@ -251,11 +251,11 @@ extern "C" int symi_route_bwd(const symi_cfg* cfg, const float* logits, const in
   route_shape(cfg->E, G, NV);
   const int grid = route_grid(cfg->T, G);
   if (NV == 1)
-    route_bwd_kernel<1><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm);
+    SYMI_TIMED(K_ROUTE_BWD, st, (route_bwd_kernel<1><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm)));
   else if (NV == 2)
-    route_bwd_kernel<2><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm);
+    SYMI_TIMED(K_ROUTE_BWD, st, (route_bwd_kernel<2><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm)));
   else
-    route_bwd_kernel<4><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm);
+    SYMI_TIMED(K_ROUTE_BWD, st, (route_bwd_kernel<4><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm)));
   SYMI_LAUNCH_CHECK("symi_route_bwd");
   return SYMI_OK;
 }
