@@ -75,6 +75,6 @@ struct WsLayout {
 WsLayout ws_layout(const symi_cfg* cfg);
 
 constexpr int DISPATCH_CHUNK = 1024;  // assignments ranked by one workgroup
-constexpr int GEMM_BM = 128;          // rows of one m-tile in the tile map
+constexpr int GEMM_BM = 256;          // rows of one m-tile in the tile map
 
 }  // namespace symi

@@ -12,14 +12,13 @@
 //   WGRAD2 dW2_e = dYp^T * H       over all rows of class e
 //   WGRAD1 dW1_e = dUV^T * Xp      over all rows of class e
 // The first four have a variable number of rows per group (one group per slot); a small
-// kernel turns slot_offsets into a table of 128-row m-tiles so that no workgroup spans
+// kernel turns slot_offsets into a table of 256-row m-tiles so that no workgroup spans
 // two slots.  The last two have a variable reduction length (the rows of a class).
 //
-// Tiles are staged in LDS with the reduction index contiguous, whatever the operand's
-// layout in HBM; operands whose reduction index is strided in memory are transposed in
-// registers (2x8 blocks) on their way into LDS.  The MFMA is issued with the weight
-// tile as its first operand, so a lane ends up with 4 consecutive output columns of one
-// output row and writes them with one vector store.
+// The MFMA is issued with the weight tile as its first operand, so a lane ends up with 4
+// consecutive output columns of one output row and writes them with one vector store.
+#include <type_traits>
+
 #include "common.h"
 
 namespace symi {
@@ -81,26 +80,46 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
 }
 
 // ---------------------------------------------------------------- bf16 MFMA kernel
-constexpr int BM = 128, BN = 128, BK = 64, LDK = BK + 8;  // LDS row stride in bf16 (pad: no bank conflicts on 16-byte reads)
-constexpr int WM = 64, WN = 64;                           // per-wavefront output tile
-constexpr int GT = 256;                                   // 4 wavefronts, 2 x 2
+// Output tile 256 x 256 per workgroup, reduction step 64, 4 wavefronts in a 2 x 2 grid,
+// each owning 128 x 128 outputs = 4 x 4 MFMA 32x32x16 tiles (256 fp32 accumulators per
+// lane).  Tiles travel HBM -> LDS with the gfx950 direct-to-LDS loads (16 bytes per
+// lane, no staging registers) into two stages of 2 x 32 KB; the next stage is in flight
+// while the current one feeds the MFMAs.  LDS bandwidth is the scarce resource at this
+// shape: 8 fragment reads of 1 KB per 16 MFMAs per wavefront.
+//
+// LDS layouts (all conflict-free for the access pattern that reads them):
+//   reduction-contiguous operand: [256 rows][64 k], 16-byte chunk c of row r stored at
+//     chunk c ^ ((r >> 1) & 7); fragments are plain 16-byte reads.
+//   reduction-strided operand (memory [k][r], r contiguous): [64 k][256 r] as loaded,
+//     16-byte chunk c of row k stored at c ^ 2*h(k), h(k) = (k & 3) | ((k >> 3) & 1) << 2;
+//     fragments come from the transposing LDS read (ds_read_b64_tr_b16), which hands
+//     lane j of a 16-lane group the four k-values of column j.
+// A direct-to-LDS load cannot zero-fill, so lanes outside the operand (row or column
+// beyond the tile's extent, reduction index beyond K) load from a block of zeros.
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int GT = 256;
 
-// Stage a [128 x 64] tile whose reduction index is contiguous in memory.
-// rowptr(i) returns the address of element (tile row i, reduction index 0) or nullptr.
-struct KcStage { uint4 v[4]; };
-// Stage a tile whose reduction index is strided: 2 (k) x 8 (r) blocks, two per thread.
-struct KsStage { uint4 v[2][2]; };
+__device__ __attribute__((aligned(16))) uint16_t g_zero_chunk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
+#define SYMI_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define SYMI_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 template <int MODE>
 __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][BM * LDK];  // [stage][A|B]
+  __shared__ __attribute__((aligned(1024))) uint16_t sA0[BM * BK];
+  __shared__ __attribute__((aligned(1024))) uint16_t sB0[BN * BK];
+  __shared__ __attribute__((aligned(1024))) uint16_t sA1[BM * BK];
+  __shared__ __attribute__((aligned(1024))) uint16_t sB1[BN * BK];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   constexpr bool VARM = MODE <= BWD_DX;
   constexpr bool A_KC = VARM;                       // left operand reduction-contiguous
   constexpr bool B_KC = MODE == FWD1 || MODE == FWD2;
 
-  int row0, row1, group, n0, kbeg = 0, K;
+  int row0, row1, group, kbeg = 0, K;
   if (VARM) {
     const int mt = blockIdx.y;
     if (mt >= p.tile_map[0]) return;
@@ -115,9 +134,9 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
     kbeg = p.slot_offsets[p.first_slot[group]];
     K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
   }
-  // FWD1 covers BN/2 hidden units per tile: each wavefront's 64 columns are 32 gate
-  // columns followed by the 32 up columns of the same hidden units.
-  n0 = blockIdx.x * (MODE == FWD1 ? BN / 2 : BN);
+  // FWD1: a tile holds 128 hidden units; every 64 tile columns are 32 gate columns
+  // followed by the 32 up columns of the same hidden units.
+  const int n0 = blockIdx.x * (MODE == FWD1 ? BN / 2 : BN);
 
   const uint16_t* A = static_cast<const uint16_t*>(p.A);
   const uint16_t* B = static_cast<const uint16_t*>(p.B) + (VARM ? (long long)group * p.b_group_stride : 0);
@@ -125,171 +144,215 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
                         : MODE == BWD_DX ? 2LL * p.f : MODE == WGRAD2 ? p.d : 2LL * p.f;
   const long long ldb = MODE == FWD1 ? p.d : MODE == FWD2 ? p.f : MODE == BWD_DH ? p.f
                         : MODE == BWD_DX ? p.d : MODE == WGRAD2 ? p.f : p.d;
+  const uint16_t* zero = g_zero_chunk;
 
-  // ---- per-thread source addresses
-  // reduction-contiguous operands: piece (row = i*32 + tid/8, k-chunk = tid%8)
-  const int pr = tid >> 3, pc = tid & 7;
-  const uint16_t* a_kc[4];
-  const uint16_t* b_kc[4];
+  // ---- direct-to-LDS loads: a wave-uniform base per reduction step plus 32-bit per-lane
+  // element offsets, one per instruction j (0..7) and operand.
+  // reduction-contiguous tile: wavefront w, instruction j fills tile rows w*64 + 8j .. +8;
+  //   lane -> (row + lane/8, physical chunk lane%8)
+  // reduction-strided tile: wavefront w, instruction j fills k-rows w*16 + 2j, +1;
+  //   lane -> (k-row + lane/32, physical chunk lane%32)
+  // Rows / column chunks beyond the operand's extent are clamped to a valid one: what
+  // they bring in only reaches outputs that are never stored.  Reduction indices beyond
+  // K (only in the last, partial step) load zeros instead.
+  // Source offsets are recomputed from four lane constants at every load (a handful of
+  // VALU ops against 4 MFMAs) instead of being kept in registers: the accumulators and
+  // fragments leave no room for 16 precomputed addresses.
+  int kc_row = wave * 64 + (lane >> 3);                        // tile row of instruction 0
+  int kc_c0 = (lane & 7) ^ ((lane >> 4) & 7);                  // logical chunk for even j
+  int ks_kb = wave * 16 + (lane >> 5);                         // k-row of instruction 0
+  int ks_c0 = (lane & 31) ^ (2 * (lane >> 5));                 // logical chunk, j-dependent bits to come
+  int f1_row = wave * 32 + (lane >> 3);                        // FWD1 weights: hidden unit of instruction 0
+
+  const uint16_t* a_base;   // element (first tile row / column, reduction index 0)
+  const uint16_t* b_base;
+  int a_lim, b_lim;         // KC: last valid tile row; KS: number of valid columns
   if (A_KC) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = row0 + i * 32 + pr;
-      a_kc[i] = r < row1 ? A + (long long)r * lda + pc * 8 : nullptr;
-    }
+    a_base = A + (long long)row0 * lda;
+    a_lim = row1 - row0 - 1;
+  } else {
+    a_base = A + (long long)kbeg * lda + row0;
+    a_lim = row1 - row0;
   }
   if (B_KC) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int j = i * 32 + pr;  // tile row of the weight operand
-      long long wrow;
-      bool ok;
-      if (MODE == FWD1) {
-        const int hu = n0 + (j >> 6) * 32 + (j & 31);   // hidden unit
-        ok = hu < p.f;
-        wrow = ((j >> 5) & 1) ? (long long)p.f + hu : hu;
-      } else {
-        wrow = n0 + j;
-        ok = wrow < p.N;
-      }
-      b_kc[i] = ok ? B + wrow * ldb + pc * 8 : nullptr;
-    }
+    b_base = MODE == FWD1 ? B : B + (long long)n0 * ldb;
+    b_lim = MODE == FWD1 ? p.f - 1 : p.N - n0 - 1;
+  } else {
+    b_base = (VARM ? B : B + (long long)kbeg * ldb) + n0;
+    b_lim = p.N - n0;
   }
-  // reduction-strided operands: block (r-chunk = tid%16, k-pair = tid/16 + 16*i)
-  const int rb = tid & 15, kp0 = tid >> 4;
-  const bool a_ks_ok = !A_KC && (row0 + rb * 8 < row1);
-  const bool b_ks_ok = !B_KC && (n0 + rb * 8 < p.N);
-  const uint16_t* a_ks = A_KC ? nullptr : A + (long long)kbeg * lda + row0 + rb * 8;
-  const uint16_t* b_ks = B_KC ? nullptr
-                              : (VARM ? B + n0 + rb * 8 : B + (long long)kbeg * ldb + n0 + rb * 8);
-
-  KcStage sa_kc, sb_kc;
-  KsStage sa_ks, sb_ks;
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
-
-  auto g_load = [&](int k0) {
-    if (A_KC) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        sa_kc.v[i] = (a_kc[i] && k0 + pc * 8 < K) ? *reinterpret_cast<const uint4*>(a_kc[i] + k0) : zero4;
-    } else {
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int k = k0 + 2 * (kp0 + 16 * i) + j;
-          sa_ks.v[i][j] = (a_ks_ok && k < K) ? *reinterpret_cast<const uint4*>(a_ks + (long long)k * lda) : zero4;
-        }
-    }
-    if (B_KC) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        sb_kc.v[i] = (b_kc[i] && k0 + pc * 8 < K) ? *reinterpret_cast<const uint4*>(b_kc[i] + k0) : zero4;
-    } else {
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int k = k0 + 2 * (kp0 + 16 * i) + j;
-          sb_ks.v[i][j] = (b_ks_ok && k < K) ? *reinterpret_cast<const uint4*>(b_ks + (long long)k * ldb) : zero4;
-        }
-    }
-  };
-
-  auto store_ks = [&](uint16_t* tile, const KsStage& s) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const uint32_t lo[4] = {s.v[i][0].x, s.v[i][0].y, s.v[i][0].z, s.v[i][0].w};
-      const uint32_t hi[4] = {s.v[i][1].x, s.v[i][1].y, s.v[i][1].z, s.v[i][1].w};
-      const int kk = 2 * (kp0 + 16 * i);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const uint32_t even = (lo[c] & 0xffffu) | (hi[c] << 16);          // r = 2c
-        const uint32_t odd = (lo[c] >> 16) | (hi[c] & 0xffff0000u);       // r = 2c+1
-        *reinterpret_cast<uint32_t*>(tile + (rb * 8 + 2 * c) * LDK + kk) = even;
-        *reinterpret_cast<uint32_t*>(tile + (rb * 8 + 2 * c + 1) * LDK + kk) = odd;
+  // LDS destination of instruction j (wave-uniform): both layouts advance 1 KB per j
+  const int wdst = wave * 8 * 512;  // elements: 8 instructions x 512 elements per wavefront
+  // q = 0..15: even = left operand, odd = right operand, instruction j = q/2
+  auto dma_one = [&](uint16_t* sA, uint16_t* sB, int k0, int q, auto tail) {
+    const int j = q >> 1;
+    const bool right = q & 1;
+    const bool kcontig = right ? B_KC : A_KC;
+    const uint16_t* base = right ? b_base : a_base;
+    const int ld = (int)(right ? ldb : lda);
+    const int lim = right ? b_lim : a_lim;
+    unsigned off;
+    int kidx;
+    if (kcontig) {
+      const int kc = kc_c0 ^ (4 * (j & 1));
+      kidx = k0 + kc * 8;
+      if (right && MODE == FWD1) {
+        // tile row t -> hidden unit n0 + (t>>7)*64 + ((t>>6)&1)*32 + (t&31), up half if (t>>5)&1
+        const int hu = min(n0 + f1_row + 8 * (j & 3), lim);
+        off = (unsigned)(((j >> 2) * p.f + hu) * ld + kc * 8);
+      } else {
+        off = (unsigned)(min(kc_row + 8 * j, lim) * ld + kc * 8);
       }
+    } else {
+      const int c = ks_c0 ^ (4 * (j & 1) + 8 * ((j >> 2) & 1));
+      kidx = k0 + ks_kb + 2 * j;
+      off = (unsigned)((ks_kb + 2 * j) * ld + (c * 8 < lim ? c : 0) * 8);
     }
-  };
-  auto store_kc = [&](uint16_t* tile, const KcStage& s) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<uint4*>(tile + (i * 32 + pr) * LDK + pc * 8) = s.v[i];
-  };
-  auto s_store = [&](int stage) {
-    if (A_KC) store_kc(lds[stage][0], sa_kc); else store_ks(lds[stage][0], sa_ks);
-    if (B_KC) store_kc(lds[stage][1], sb_kc); else store_ks(lds[stage][1], sb_ks);
+    const uint16_t* src = (kcontig ? base + k0 : base + (long long)k0 * ld) + (size_t)off;
+    if (decltype(tail)::value) {
+      if (kidx >= K) src = zero;
+    }
+    __builtin_amdgcn_global_load_lds(SYMI_GPTR(src), SYMI_LPTR((right ? sB : sA) + wdst + j * 512), 16, 0, 0);
   };
 
-  floatx16 acc[2][2];
+  // ---- fragment addresses (element offsets inside a stage)
+  // KC: row (sub*32 + lane%32), chunk (2*ks + lane/32) ^ ((lane%32 >> 1) & 7)
+  const int r31 = lane & 31;
+  int kc_off[4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int ks = 0; ks < 4; ++ks) kc_off[ks] = r31 * BK + (((2 * ks + (lane >> 5)) ^ ((r31 >> 1) & 7)) * 8);
+  // KS: lane = 16*g + jj supplies the address of k-row (16*ks + 8*(g>>1) + 4*e + jj/4),
+  // 8-byte piece (jj%4) of columns sub*32 + 16*(g&1) ..; it receives column sub*32 + lane%32
+  const int g4 = lane >> 4, jj = lane & 15;
+  const int ks_h2 = 2 * ((jj >> 2) | ((g4 >> 1) << 2));
+  const int ks_row = (8 * (g4 >> 1) + (jj >> 2)) * 256;
+  int ks_col[4];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+  for (int sub = 0; sub < 4; ++sub)
+    ks_col[sub] = (((4 * sub + 2 * (g4 & 1) + ((jj & 3) >> 1)) ^ ks_h2) * 8) + 4 * (jj & 1);
+
+  auto frag = [&](const uint16_t* tile, bool kc, int wbase_rows, int sub, int ks) -> bf16x8 {
+    if (kc) {
+      return *reinterpret_cast<const bf16x8*>(tile + (wbase_rows + sub * 32) * BK + kc_off[ks]);
+    } else {
+      const uint16_t* q = tile + ks_row + ks * 16 * 256 + wbase_rows + ks_col[sub];
+      const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) shortx4*)SYMI_LPTR(q));
+      const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) shortx4*)SYMI_LPTR(q + 4 * 256));
+      union { shortx4 h[2]; bf16x8 v; } u;
+      u.h[0] = lo;
+      u.h[1] = hi;
+      return u.v;
+    }
+  };
+
+  floatx16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = (K + BK - 1) / BK;
-  if (nk > 0) {
-    g_load(0);
-    s_store(0);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) g_load((kt + 1) * BK);
-    const uint16_t* At = lds[cur][0] + (wm * WM + (lane & 31)) * LDK + (lane >> 5) * 8;
-    const uint16_t* Bt = lds[cur][1] + (wn * WN + (lane & 31)) * LDK + (lane >> 5) * 8;
+  const int nfull = K / BK;   // steps before the (optional) partial one
+  // computes stage (At, Bt); PRE = 1 loads full step `next` into (nA, nB) meanwhile,
+  // PRE = 2 loads the partial last step (zero-filled beyond K), PRE = 0 loads nothing
+  auto tile_step = [&](const uint16_t* At, const uint16_t* Bt, uint16_t* nA, uint16_t* nB, int next,
+                       auto pre) {
+    constexpr int PRE = decltype(pre)::value;
+    // keep the address arithmetic of the loads inside the step (see dma_one)
+    asm volatile("" : "+v"(kc_row), "+v"(kc_c0), "+v"(ks_kb), "+v"(ks_c0), "+v"(f1_row));
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[2], bf[2];
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[4], bfr[4];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        af[i] = *reinterpret_cast<const bf16x8*>(At + i * 32 * LDK + ks * 16);
-        bf[i] = *reinterpret_cast<const bf16x8*>(Bt + i * 32 * LDK + ks * 16);
+      for (int i = 0; i < 4; ++i) {
+        af[i] = frag(At, A_KC, wm * 128, i, ks);
+        bfr[i] = frag(Bt, B_KC, wn * 128, i, ks);
       }
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 4; ++i) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        if (PRE == 1) dma_one(nA, nB, next * BK, ks * 4 + i, std::false_type{});
+        if (PRE == 2) dma_one(nA, nB, next * BK, ks * 4 + i, std::true_type{});
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    if (kt + 1 < nk) s_store(cur ^ 1);
-    __syncthreads();
+  };
+  using Pre0 = std::integral_constant<int, 0>;
+  using Pre1 = std::integral_constant<int, 1>;
+  using Pre2 = std::integral_constant<int, 2>;
+  if (nk > 0) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      if (nfull > 0) dma_one(sA0, sB0, 0, q, std::false_type{});
+      else dma_one(sA0, sB0, 0, q, std::true_type{});
+    }
+  }
+  int t = 0;
+  // branch-free main loop: two steps per trip, both prefetching full steps
+  for (; t + 2 < nfull; t += 2) {
+    wait_vmcnt0();
+    __builtin_amdgcn_s_barrier();
+    tile_step(sA0, sB0, sA1, sB1, t + 1, Pre1{});
+    wait_vmcnt0();
+    __builtin_amdgcn_s_barrier();
+    tile_step(sA1, sB1, sA0, sB0, t + 2, Pre1{});
+  }
+  // the last (up to three) steps
+  for (; t < nk; ++t) {
+    wait_vmcnt0();
+    __builtin_amdgcn_s_barrier();
+    const int pre = t + 1 >= nk ? 0 : (t + 1 < nfull ? 1 : 2);
+    if (t & 1) {
+      if (pre == 1) tile_step(sA1, sB1, sA0, sB0, t + 1, Pre1{});
+      else if (pre == 2) tile_step(sA1, sB1, sA0, sB0, t + 1, Pre2{});
+      else tile_step(sA1, sB1, sA0, sB0, t + 1, Pre0{});
+    } else {
+      if (pre == 1) tile_step(sA0, sB0, sA1, sB1, t + 1, Pre1{});
+      else if (pre == 2) tile_step(sA0, sB0, sA1, sB1, t + 1, Pre2{});
+      else tile_step(sA0, sB0, sA1, sB1, t + 1, Pre0{});
+    }
   }
 
   // ---- epilogue: lane owns output row (lane%32) and 4 consecutive columns per r/4
   const int colq = (lane >> 5) * 4;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int row = row0 + wm * WM + i * 32 + (lane & 31);
+  for (int i = 0; i < 4; ++i) {
+    const int row = row0 + wm * 128 + i * 32 + (lane & 31);
     if (row >= row1) continue;
     if (MODE == FWD1) {
       uint16_t* UVo = static_cast<uint16_t*>(p.UVout);
       uint16_t* Ho = static_cast<uint16_t*>(p.H);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int hu = n0 + wn * 32 + g * 8 + colq;
-        if (hu >= p.f) continue;
-        float u[4], v[4], h[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          u[c] = acc[i][0][g * 4 + c];
-          v[c] = acc[i][1][g * 4 + c];
-          h[c] = silu_f(u[c]) * v[c];
-        }
-        const long long o = (long long)row * 2 * p.f + hu;
-        *reinterpret_cast<uint2*>(UVo + o) = make_uint2(pack_bf16x2(u[0], u[1]), pack_bf16x2(u[2], u[3]));
-        *reinterpret_cast<uint2*>(UVo + o + p.f) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-        *reinterpret_cast<uint2*>(Ho + (long long)row * p.f + hu) =
-            make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int col = n0 + wn * WN + j * 32 + g * 8 + colq;
+          const int hu = n0 + wn * 64 + hb * 32 + g * 8 + colq;
+          if (hu >= p.f) continue;
+          float u[4], v[4], h[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            u[c] = acc[i][2 * hb][g * 4 + c];
+            v[c] = acc[i][2 * hb + 1][g * 4 + c];
+            h[c] = silu_f(u[c]) * v[c];
+          }
+          const long long o = (long long)row * 2 * p.f + hu;
+          *reinterpret_cast<uint2*>(UVo + o) = make_uint2(pack_bf16x2(u[0], u[1]), pack_bf16x2(u[2], u[3]));
+          *reinterpret_cast<uint2*>(UVo + o + p.f) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          *reinterpret_cast<uint2*>(Ho + (long long)row * p.f + hu) =
+              make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+        }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = n0 + wn * 128 + j * 32 + g * 8 + colq;
           if (col >= p.N) continue;
           const float x0 = acc[i][j][g * 4], x1 = acc[i][j][g * 4 + 1], x2 = acc[i][j][g * 4 + 2],
                       x3 = acc[i][j][g * 4 + 3];
@@ -339,10 +402,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
   constexpr bool VARM = MODE <= BWD_DX;
   int row0, row1, group, kbeg = 0, K;
   if (VARM) {
-    // fp32 tiles are 64 rows: each 128-row entry of the table is walked in two halves
-    const int mt = blockIdx.y >> 1;
+    // fp32 tiles are 64 rows: each 256-row entry of the table is walked in four quarters
+    const int mt = blockIdx.y >> 2;
     if (mt >= p.tile_map[0]) return;
-    row0 = p.tile_map[4 + 4 * mt] + (blockIdx.y & 1) * FB;
+    row0 = p.tile_map[4 + 4 * mt] + (blockIdx.y & 3) * FB;
     row1 = p.tile_map[4 + 4 * mt + 1];
     if (row0 >= row1) return;
     row1 = min(row1, row0 + FB);
@@ -471,7 +534,7 @@ static void launch_gemm(const symi_cfg* cfg, const GemmParams& p, int n_cols, in
     SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_bf16_kernel<MODE><<<grid, GT, 0, st>>>(p)));
   } else {
     const int bn = MODE == FWD1 ? FB / 2 : FB;
-    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 2 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : cfg->E);
+    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 4 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : cfg->E);
     SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_f32_kernel<MODE><<<grid, 256, 0, st>>>(p)));
   }
 }
