@@ -48,6 +48,10 @@ struct GemmParams {
 
 __device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
 __device__ __forceinline__ float sigmoid_f(float u) { return 1.f / (1.f + expf(-u)); }
+// bf16 path: hardware exp2/rcp (relative error ~1e-6, far below the bf16 rounding of the result)
+__device__ __forceinline__ float sigmoid_fast(float u) {
+  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * u));
+}
 
 // ---------------------------------------------------------------- m-tile table
 __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ slot_offsets,
@@ -256,12 +260,10 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = (K + BK - 1) / BK;
-  const int nfull = K / BK;   // steps before the (optional) partial one
-  // computes stage (At, Bt); PRE = 1 loads full step `next` into (nA, nB) meanwhile,
-  // PRE = 2 loads the partial last step (zero-filled beyond K), PRE = 0 loads nothing
-  auto tile_step = [&](const uint16_t* At, const uint16_t* Bt, uint16_t* nA, uint16_t* nB, int next,
-                       auto pre) {
-    constexpr int PRE = decltype(pre)::value;
+  // computes stage (At, Bt) while reduction step `next` is loaded into (nA, nB); beyond
+  // the last step every lane loads zeros (a dummy that keeps the loop free of branches,
+  // which is what lets the 256 accumulators stay put in their registers)
+  auto tile_step = [&](const uint16_t* At, const uint16_t* Bt, uint16_t* nA, uint16_t* nB, int next) {
     // keep the address arithmetic of the loads inside the step (see dma_one)
     asm volatile("" : "+v"(kc_row), "+v"(kc_c0), "+v"(ks_kb), "+v"(ks_c0), "+v"(f1_row));
 #pragma unroll
@@ -277,47 +279,26 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-        if (PRE == 1) dma_one(nA, nB, next * BK, ks * 4 + i, std::false_type{});
-        if (PRE == 2) dma_one(nA, nB, next * BK, ks * 4 + i, std::true_type{});
+        dma_one(nA, nB, next * BK, ks * 4 + i, std::true_type{});
         __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
-  using Pre0 = std::integral_constant<int, 0>;
-  using Pre1 = std::integral_constant<int, 1>;
-  using Pre2 = std::integral_constant<int, 2>;
   if (nk > 0) {
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      if (nfull > 0) dma_one(sA0, sB0, 0, q, std::false_type{});
-      else dma_one(sA0, sB0, 0, q, std::true_type{});
-    }
+    for (int q = 0; q < 16; ++q) dma_one(sA0, sB0, 0, q, std::true_type{});
   }
-  int t = 0;
-  // branch-free main loop: two steps per trip, both prefetching full steps
-  for (; t + 2 < nfull; t += 2) {
+  for (int t = 0; t < nk; t += 2) {
     wait_vmcnt0();
     __builtin_amdgcn_s_barrier();
-    tile_step(sA0, sB0, sA1, sB1, t + 1, Pre1{});
+    tile_step(sA0, sB0, sA1, sB1, t + 1);
+    // always a pair: for an odd step count the second stage holds the zeros of the dummy
+    // load and adds nothing (a mid-loop exit would cost more than the idle step)
     wait_vmcnt0();
     __builtin_amdgcn_s_barrier();
-    tile_step(sA1, sB1, sA0, sB0, t + 2, Pre1{});
+    tile_step(sA1, sB1, sA0, sB0, t + 2);
   }
-  // the last (up to three) steps
-  for (; t < nk; ++t) {
-    wait_vmcnt0();
-    __builtin_amdgcn_s_barrier();
-    const int pre = t + 1 >= nk ? 0 : (t + 1 < nfull ? 1 : 2);
-    if (t & 1) {
-      if (pre == 1) tile_step(sA1, sB1, sA0, sB0, t + 1, Pre1{});
-      else if (pre == 2) tile_step(sA1, sB1, sA0, sB0, t + 1, Pre2{});
-      else tile_step(sA1, sB1, sA0, sB0, t + 1, Pre0{});
-    } else {
-      if (pre == 1) tile_step(sA0, sB0, sA1, sB1, t + 1, Pre1{});
-      else if (pre == 2) tile_step(sA0, sB0, sA1, sB1, t + 1, Pre2{});
-      else tile_step(sA0, sB0, sA1, sB1, t + 1, Pre0{});
-    }
-  }
+  wait_vmcnt0();   // the dummy loads of the last step
 
   // ---- epilogue: lane owns output row (lane%32) and 4 consecutive columns per r/4
   const int colq = (lane >> 5) * 4;
@@ -339,13 +320,14 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
           for (int c = 0; c < 4; ++c) {
             u[c] = acc[i][2 * hb][g * 4 + c];
             v[c] = acc[i][2 * hb + 1][g * 4 + c];
-            h[c] = silu_f(u[c]) * v[c];
+            h[c] = u[c] * sigmoid_fast(u[c]) * v[c];
           }
           const long long o = (long long)row * 2 * p.f + hu;
           *reinterpret_cast<uint2*>(UVo + o) = make_uint2(pack_bf16x2(u[0], u[1]), pack_bf16x2(u[2], u[3]));
           *reinterpret_cast<uint2*>(UVo + o + p.f) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
           *reinterpret_cast<uint2*>(Ho + (long long)row * p.f + hu) =
               make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+          __builtin_amdgcn_sched_barrier(0);   // keep the epilogue's register footprint small
         }
     } else {
 #pragma unroll
@@ -374,7 +356,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
             float du[4], dv[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-              const float sg = sigmoid_f(u[c]);
+              const float sg = sigmoid_fast(u[c]);
               du[c] = dh[c] * v[c] * sg * (1.f + u[c] * (1.f - sg));
               dv[c] = dh[c] * u[c] * sg;
             }
@@ -384,6 +366,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
             float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride;
             *reinterpret_cast<float4*>(Co + (long long)row * p.N + col) = make_float4(x0, x1, x2, x3);
           }
+          __builtin_amdgcn_sched_barrier(0);   // keep the epilogue's register footprint small
         }
     }
   }
