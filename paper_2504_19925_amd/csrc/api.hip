@@ -60,6 +60,8 @@ WsLayout ws_layout(const symi_cfg* c) {
   off += align_up((4 + 4 * mtiles) * sizeof(int32_t), 256);
   L.duv = off;
   off += align_up(A * 2 * c->f * w, 256);
+  L.dh = off;
+  off += align_up(A * c->f * w, 256);
   L.total = off + 256;
   return L;
 }
@@ -72,7 +74,8 @@ static hipEvent_t g_open[K_COUNT];
 static const char* const g_names[K_COUNT] = {
     "fill_i32", "route", "route_bwd", "place", "chunk_count", "chunk_scan", "chunk_rank",
     "gather_rows", "tile_map", "gemm_fwd1", "gemm_fwd2", "gemm_bwd_dh", "gemm_bwd_dx",
-    "gemm_wgrad2", "gemm_wgrad1", "combine", "combine_bwd", "dispatch_bwd", "adam_to_replicas"};
+    "gemm_wgrad2", "gemm_wgrad1", "combine", "combine_bwd", "dispatch_bwd", "adam_to_replicas",
+    "dswiglu"};
 
 void timing_begin(int kid, hipStream_t st) {
   hipEvent_t e;

@@ -7,7 +7,7 @@
 // MFMA 32x32x16 bf16 instruction; a plain-FMA twin serves fp32 configurations):
 //   FWD1   [u|v] = Xp  * W1^T      + SwiGLU epilogue writing u, v and h = silu(u)*v
 //   FWD2   Yp    = H   * W2^T
-//   BWD_DH dh    = dYp * W2        + epilogue turning dh into du, dv (never stored as dh)
+//   BWD_DH dh    = dYp * W2        then du, dv from dh, u, v (streaming kernel; fused epilogue in fp32)
 //   BWD_DX dXp   = dUV * W1
 //   WGRAD2 dW2_e = dYp^T * H       over all rows of class e
 //   WGRAD1 dW1_e = dUV^T * Xp      over all rows of class e
@@ -141,6 +141,18 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   // FWD1: a tile holds 128 hidden units; every 64 tile columns are 32 gate columns
   // followed by the 32 up columns of the same hidden units.
   const int n0 = blockIdx.x * (MODE == FWD1 ? BN / 2 : BN);
+
+  if (!VARM && K == 0) {
+    // a class without rows: its gradient tile is zero; stream it out with one 1 KB row
+    // segment per wavefront store
+    float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride;
+    const int col = n0 + lane * 4;
+    if (col < p.N) {
+      for (int r = row0 + wave; r < row1; r += GT / 64)
+        *reinterpret_cast<float4*>(Co + (long long)r * p.N + col) = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    return;
+  }
 
   const uint16_t* A = static_cast<const uint16_t*>(p.A);
   const uint16_t* B = static_cast<const uint16_t*>(p.B) + (VARM ? (long long)group * p.b_group_stride : 0);
@@ -327,7 +339,6 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
           *reinterpret_cast<uint2*>(UVo + o + p.f) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
           *reinterpret_cast<uint2*>(Ho + (long long)row * p.f + hu) =
               make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
-          __builtin_amdgcn_sched_barrier(0);   // keep the epilogue's register footprint small
         }
     } else {
 #pragma unroll
@@ -338,37 +349,54 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
           if (col >= p.N) continue;
           const float x0 = acc[i][j][g * 4], x1 = acc[i][j][g * 4 + 1], x2 = acc[i][j][g * 4 + 2],
                       x3 = acc[i][j][g * 4 + 3];
-          if (MODE == FWD2 || MODE == BWD_DX) {
+          if (MODE == FWD2 || MODE == BWD_DX || MODE == BWD_DH) {
             uint16_t* Co = static_cast<uint16_t*>(p.C);
             *reinterpret_cast<uint2*>(Co + (long long)row * p.N + col) =
                 make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
-          } else if (MODE == BWD_DH) {
-            const uint16_t* UVi = static_cast<const uint16_t*>(p.UV);
-            uint16_t* Co = static_cast<uint16_t*>(p.C);  // dUV
-            const long long o = (long long)row * 2 * p.f + col;
-            const uint2 uu = *reinterpret_cast<const uint2*>(UVi + o);
-            const uint2 vv = *reinterpret_cast<const uint2*>(UVi + o + p.f);
-            const float dh[4] = {x0, x1, x2, x3};
-            const float u[4] = {__uint_as_float(uu.x << 16), __uint_as_float(uu.x & 0xffff0000u),
-                                __uint_as_float(uu.y << 16), __uint_as_float(uu.y & 0xffff0000u)};
-            const float v[4] = {__uint_as_float(vv.x << 16), __uint_as_float(vv.x & 0xffff0000u),
-                                __uint_as_float(vv.y << 16), __uint_as_float(vv.y & 0xffff0000u)};
-            float du[4], dv[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              const float sg = sigmoid_fast(u[c]);
-              du[c] = dh[c] * v[c] * sg * (1.f + u[c] * (1.f - sg));
-              dv[c] = dh[c] * u[c] * sg;
-            }
-            *reinterpret_cast<uint2*>(Co + o) = make_uint2(pack_bf16x2(du[0], du[1]), pack_bf16x2(du[2], du[3]));
-            *reinterpret_cast<uint2*>(Co + o + p.f) = make_uint2(pack_bf16x2(dv[0], dv[1]), pack_bf16x2(dv[2], dv[3]));
           } else {  // weight gradients, fp32
             float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride;
             *reinterpret_cast<float4*>(Co + (long long)row * p.N + col) = make_float4(x0, x1, x2, x3);
           }
-          __builtin_amdgcn_sched_barrier(0);   // keep the epilogue's register footprint small
         }
     }
+    __builtin_amdgcn_sched_barrier(0);   // one 32-row block at a time: bounds the registers in flight
+  }
+}
+
+// du, dv from dh and the saved u, v (bf16 path; the fp32 twin fuses this into its epilogue):
+// du = dh * v * s * (1 + u * (1 - s)), dv = dh * u * s, s = sigmoid(u).  Pure streaming,
+// 16-byte pieces: 6 B read and 4 B written per hidden activation.
+__global__ __launch_bounds__(256) void dswiglu_bf16_kernel(const uint4* __restrict__ dH,
+                                                           const uint4* __restrict__ UV,
+                                                           uint4* __restrict__ dUV, long long rows,
+                                                           int f8) {
+  const long long n = rows * f8;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+    const long long r = i / f8;
+    const int c = (int)(i - r * f8);
+    const uint4 dh = dH[i];
+    const uint4 uu = UV[r * 2 * f8 + c];
+    const uint4 vv = UV[r * 2 * f8 + f8 + c];
+    const uint32_t dw[4] = {dh.x, dh.y, dh.z, dh.w}, uw[4] = {uu.x, uu.y, uu.z, uu.w},
+                   vw[4] = {vv.x, vv.y, vv.z, vv.w};
+    uint32_t du[4], dv[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float o_du[2], o_dv[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const float d_ = __uint_as_float(h ? (dw[q] & 0xffff0000u) : (dw[q] << 16));
+        const float u_ = __uint_as_float(h ? (uw[q] & 0xffff0000u) : (uw[q] << 16));
+        const float v_ = __uint_as_float(h ? (vw[q] & 0xffff0000u) : (vw[q] << 16));
+        const float sg = sigmoid_fast(u_);
+        o_du[h] = d_ * v_ * sg * (1.f + u_ * (1.f - sg));
+        o_dv[h] = d_ * u_ * sg;
+      }
+      du[q] = pack_bf16x2(o_du[0], o_du[1]);
+      dv[q] = pack_bf16x2(o_dv[0], o_dv[1]);
+    }
+    dUV[r * 2 * f8 + c] = make_uint4(du[0], du[1], du[2], du[3]);
+    dUV[r * 2 * f8 + f8 + c] = make_uint4(dv[0], dv[1], dv[2], dv[3]);
   }
 }
 
@@ -583,10 +611,19 @@ extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void*
   if (A > 0) {
     SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, cfg->S_tot, map)));
     // dh = dYp W2, then du, dv
-    p.A = dYp; p.B = W2_slots; p.C = dUV; p.UV = UV;
+    const bool bf16 = cfg->dtype == SYMI_BF16;
+    void* dHbuf = static_cast<char*>(ws) + L.dh;
+    p.A = dYp; p.B = W2_slots; p.C = bf16 ? dHbuf : dUV; p.UV = UV;
     p.b_group_stride = (long long)cfg->d * cfg->f;
     p.N = cfg->f; p.K = cfg->d;
     launch_gemm<BWD_DH>(cfg, p, cfg->f, max_mtiles, st);
+    if (bf16) {
+      const long long pieces = A * (cfg->f / 8);
+      long long g = (pieces + 255) / 256;
+      if (g > 16384) g = 16384;
+      SYMI_TIMED(K_DSWIGLU, st, (dswiglu_bf16_kernel<<<(unsigned)g, 256, 0, st>>>(
+          static_cast<const uint4*>(dHbuf), static_cast<const uint4*>(UV), static_cast<uint4*>(dUV), A, cfg->f / 8)));
+    }
     // dXp = dUV W1
     p.A = dUV; p.B = W1_slots; p.C = dXp;
     p.b_group_stride = 2LL * cfg->f * cfg->d;
