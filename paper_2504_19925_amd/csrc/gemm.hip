@@ -95,7 +95,8 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
 //   reduction-contiguous operand: [256 rows][64 k], 16-byte chunk c of row r stored at
 //     chunk c ^ ((r >> 1) & 7); fragments are plain 16-byte reads.
 //   reduction-strided operand (memory [k][r], r contiguous): [64 k][256 r] as loaded,
-//     16-byte chunk c of row k stored at c ^ 2*h(k), h(k) = (k & 3) | ((k >> 3) & 1) << 2;
+//     16-byte chunk c of row k stored at c ^ 10*(k & 1) ^ 4*((k >> 1) & 1): the 32 lanes
+//     the LDS serves per cycle (4 k-rows x 64 B) then fall into 64 distinct banks;
 //     fragments come from the transposing LDS read (ds_read_b64_tr_b16), which hands
 //     lane j of a 16-lane group the four k-values of column j.
 // A direct-to-LDS load cannot zero-fill, so lanes outside the operand (row or column
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   int kc_row = wave * 64 + (lane >> 3);                        // tile row of instruction 0
   int kc_c0 = (lane & 7) ^ ((lane >> 4) & 7);                  // logical chunk for even j
   int ks_kb = wave * 16 + (lane >> 5);                         // k-row of instruction 0
-  int ks_c0 = (lane & 31) ^ (2 * (lane >> 5));                 // logical chunk, j-dependent bits to come
+  int ks_c0 = (lane & 31) ^ (10 * (lane >> 5));                // logical chunk, j-dependent bits to come
   int f1_row = wave * 32 + (lane >> 3);                        // FWD1 weights: hidden unit of instruction 0
 
   const uint16_t* a_base;   // element (first tile row / column, reduction index 0)
@@ -220,7 +221,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
         off = (unsigned)(min(kc_row + 8 * j, lim) * ld + kc * 8);
       }
     } else {
-      const int c = ks_c0 ^ (4 * (j & 1) + 8 * ((j >> 2) & 1));
+      const int c = ks_c0 ^ (4 * (j & 1));
       kidx = k0 + ks_kb + 2 * j;
       off = (unsigned)((ks_kb + 2 * j) * ld + (c * 8 < lim ? c : 0) * 8);
     }
@@ -240,7 +241,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   // KS: lane = 16*g + jj supplies the address of k-row (16*ks + 8*(g>>1) + 4*e + jj/4),
   // 8-byte piece (jj%4) of columns sub*32 + 16*(g&1) ..; it receives column sub*32 + lane%32
   const int g4 = lane >> 4, jj = lane & 15;
-  const int ks_h2 = 2 * ((jj >> 2) | ((g4 >> 1) << 2));
+  const int ks_h2 = (10 * ((jj >> 2) & 1)) ^ (4 * ((jj >> 3) & 1));   // swizzle of this lane's k-row
   const int ks_row = (8 * (g4 >> 1) + (jj >> 2)) * 256;
   int ks_col[4];
 #pragma unroll
