@@ -248,15 +248,23 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   for (int sub = 0; sub < 4; ++sub)
     ks_col[sub] = (((4 * sub + 2 * (g4 & 1) + ((jj & 3) >> 1)) ^ ks_h2) * 8) + 4 * (jj & 1);
 
+  // The transposing reads are issued as inline assembly: the compiler would otherwise
+  // order every such read after all direct-to-LDS loads in flight (it cannot tell the two
+  // stages apart) and stall on the prefetch it was meant to overlap.  Their completion is
+  // awaited by hand (lgkmcnt(0)) before the MFMAs that consume them.
   auto frag = [&](const uint16_t* tile, bool kc, int wbase_rows, int sub, int ks) -> bf16x8 {
     if (kc) {
       return *reinterpret_cast<const bf16x8*>(tile + (wbase_rows + sub * 32) * BK + kc_off[ks]);
     } else {
-      const uint16_t* q = tile + ks_row + ks * 16 * 256 + wbase_rows + ks_col[sub];
-      const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) shortx4*)SYMI_LPTR(q));
-      const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) shortx4*)SYMI_LPTR(q + 4 * 256));
+      const unsigned addr =
+          (unsigned)(size_t)SYMI_LPTR(tile) + 2u * (unsigned)(ks_row + wbase_rows + ks_col[sub]);
+      shortx4 lo, hi;
+      switch (ks) {   // the k-step is an immediate offset: 16 k-rows of 512 bytes
+        case 0: asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:2048" : "=&v"(lo), "=&v"(hi) : "v"(addr)); break;
+        case 1: asm volatile("ds_read_b64_tr_b16 %0, %2 offset:8192\n\tds_read_b64_tr_b16 %1, %2 offset:10240" : "=&v"(lo), "=&v"(hi) : "v"(addr)); break;
+        case 2: asm volatile("ds_read_b64_tr_b16 %0, %2 offset:16384\n\tds_read_b64_tr_b16 %1, %2 offset:18432" : "=&v"(lo), "=&v"(hi) : "v"(addr)); break;
+        default: asm volatile("ds_read_b64_tr_b16 %0, %2 offset:24576\n\tds_read_b64_tr_b16 %1, %2 offset:26624" : "=&v"(lo), "=&v"(hi) : "v"(addr)); break;
+      }
       union { shortx4 h[2]; bf16x8 v; } u;
       u.h[0] = lo;
       u.h[1] = hi;
@@ -286,6 +294,10 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
       for (int i = 0; i < 4; ++i) {
         af[i] = frag(At, A_KC, wm * 128, i, ks);
         bfr[i] = frag(Bt, B_KC, wn * 128, i, ks);
+      }
+      if (!A_KC || !B_KC) {
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): the hand-issued transposing reads
+        __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
