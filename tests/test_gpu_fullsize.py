@@ -1,0 +1,124 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot run a whole full-size layer in seconds, so floating-point outputs are
+checked on samples it can compute one by one, using two facts of the definition:
+  * tokens are independent: Y[t], dX[t], dgate[t], dlogits[t] of a sampled token equal the
+    oracle's result on the batch made of the sampled tokens alone;
+  * hidden units are independent in the weight gradient: dW restricted to a few hidden
+    units equals the gradient of the FFN that keeps only those units (pinned on the CPU in
+    test_oracle_layer_adam.py), so the oracle runs ALL tokens through 4..8-unit experts.
+Integer outputs are compared in full, bit for bit; the Adam state of the whole shard is
+compared in full."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import symi_oracle as O
+from tests import harness as Hn
+from tests.util import TOL, check_close, relerr_elem
+
+pytestmark = pytest.mark.gpu
+
+N_TOKENS = 48      # sampled tokens per config
+N_UNITS = {"c2": 8, "c3": 8, "c4": 6, "c5": 4}
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+@pytest.mark.timeout(900)
+def test_fullsize_sampled_parity(name):
+    c = wl.get_config(name)
+    print(f"[fullsize] {name}: T={c.T} E={c.E} k={c.k} d={c.d} f={c.f} S_tot={c.S_tot} N={c.N}", flush=True)
+    rng = np.random.default_rng(1234 + c.seed)
+    st = Hn.State(c, shard=c.N - 1)
+    cfg = st.cfg
+    it = 1 if c.iters > 1 else 0
+    X, logits, dY = Hn.draw_inputs(c, it)
+    if name != "c2":
+        # placement that mimics this very popularity: hot classes own many replicas
+        import paper_2504_19925_amd as symi
+        symi.symi_route(cfg, logits, st.idx, st.gate, st.hist)
+        st.hist_prev.copy_(st.hist)
+    # c2 keeps the empty history -> uniform placement -> hot classes squeezed into one slot
+    hist_prev = st.hist_prev.cpu().numpy()
+    st.place_current()
+    st.forward(X, logits)
+    st.backward(dY, logits)
+    adam, hp = Hn.make_adam(step=3, weight_decay=0.01)
+    st.m.normal_(generator=torch.Generator(device="cuda").manual_seed(7)).mul_(1e-3)
+    st.v.uniform_(1e-8, 1e-6, generator=torch.Generator(device="cuda").manual_seed(8))
+    master0, m0, v0 = st.master.clone(), st.m.clone(), st.v.clone()
+    st.optimizer(adam)
+    Hn.sync()
+    print("[fullsize] GPU done", flush=True)
+
+    # ---- integers, in full
+    zn = Hn.npf(logits)
+    o_counts, o_place, o_first = O.place(hist_prev, c.S_tot)
+    o_idx, o_gate, o_hist = O.route(zn, c.k, True)
+    o_roa, o_aor, o_off = O.dispatch(o_idx, o_counts, o_first)
+    n_counts, n_place, n_first = O.place(o_hist, c.S_tot)
+    for got, want in [(st.counts, o_counts), (st.placement, o_place), (st.first_slot, o_first),
+                      (st.idx, o_idx), (st.hist, o_hist), (st.row_of_assign, o_roa),
+                      (st.assign_of_row, o_aor), (st.slot_offsets, o_off),
+                      (st.counts_next, n_counts), (st.placement_next, n_place),
+                      (st.first_slot_next, n_first)]:
+        assert (got.cpu().numpy() == want).all()
+    assert torch.equal(st.Xp, X[(st.assign_of_row // c.k).long()])
+    assert relerr_elem(Hn.npf(st.gate), o_gate) <= TOL["f32"]
+    print(f"[fullsize] integers ok; slot rows min/max = {np.diff(o_off).min()}/{np.diff(o_off).max()}, "
+          f"replicas max = {o_counts.max()}", flush=True)
+
+    # ---- sampled tokens: Y, dX, dgate, dlogits
+    ts = np.sort(rng.choice(c.T, size=N_TOKENS, replace=False))
+    tt = torch.tensor(ts, device="cuda")
+    W1L, W2L = Hn.LazyWeights(st.W1c), Hn.LazyWeights(st.W2c)
+    Xs, dYs, zs = Hn.npf(X[tt]), Hn.npf(dY[tt]), zn[ts]
+    Ys = O.moe_forward(Xs, o_idx[ts], o_gate[ts], W1L, W2L)
+    dXs, _, _, dgs = O.moe_backward(Xs, o_idx[ts], o_gate[ts], W1L, W2L, dYs)
+    dls = O.route_backward(zs, o_idx[ts], o_gate[ts], dgs, True)
+    log = {}
+    check_close("Y", Hn.npf(st.Y[tt]), Ys, c.dtype, log=log)
+    check_close("dX", Hn.npf(st.dX[tt]), dXs, c.dtype, log=log)
+    check_close("dgate", Hn.npf(st.dgate[tt]), dgs, c.dtype, log=log)
+    check_close("dlogits", Hn.npf(st.dlogits[tt]), dls, c.dtype, log=log)
+    print("[fullsize] tokens " + " ".join(f"{k}:max={v['max']:.2e},l2={v['l2']:.2e}" for k, v in log.items()),
+          flush=True)
+
+    # ---- sampled hidden units: dW1 rows (gate and up) and dW2 columns of every class
+    hs = np.sort(rng.choice(c.f, size=N_UNITS[name], replace=False))
+    hcat = np.concatenate([hs, c.f + hs])
+    W1S = Hn.LazyWeights(st.W1c, rows=torch.tensor(hcat, device="cuda"))
+    W2S = Hn.LazyWeights(st.W2c, cols=torch.tensor(hs, device="cuda"))
+    _, dW1s, dW2s, _ = O.moe_backward(Hn.npf(X), o_idx, o_gate, W1S, W2S, Hn.npf(dY))
+    g1 = Hn.npf(st.dW1[:, torch.tensor(hcat, device="cuda"), :])
+    g2 = Hn.npf(st.dW2[:, :, torch.tensor(hs, device="cuda")])
+    log = {}
+    check_close("dW1", g1, dW1s, c.dtype, group_axis=0, log=log)
+    check_close("dW2", g2, dW2s, c.dtype, group_axis=0, log=log)
+    print("[fullsize] units " + " ".join(f"{k}:max={v['max']:.2e},l2={v['l2']:.2e}" for k, v in log.items()),
+          flush=True)
+    for e in np.nonzero(o_hist == 0)[0][:4]:
+        assert not st.dW1[e].any() and not st.dW2[e].any()
+
+    # ---- Adam on the whole shard, fed the GPU's own gradients; replica slots
+    per = c.P_e // c.N
+    lo = cfg.shard * per
+    gflat = torch.cat([st.dW1.reshape(c.E, -1)[:, lo:min(lo + per, 2 * c.f * c.d)],
+                       st.dW2.reshape(c.E, -1)[:, max(lo - 2 * c.f * c.d, 0):max(lo + per - 2 * c.f * c.d, 0)]], 1)
+    assert gflat.shape[1] == per
+    for e0 in range(0, c.E, 16):            # in slabs, to bound the host's fp64 copies
+        sl = slice(e0, min(e0 + 16, c.E))
+        w2, m2, v2 = O.adam_step(Hn.npf(master0[sl]), Hn.npf(m0[sl]), Hn.npf(v0[sl]), Hn.npf(gflat[sl]),
+                                 hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"],
+                                 hp["grad_scale"], hp["step"])
+        assert relerr_elem(Hn.npf(st.master[sl]), w2) <= TOL["adam"]
+        assert relerr_elem(Hn.npf(st.m[sl]), m2) <= TOL["adam"]
+        assert relerr_elem(Hn.npf(st.v[sl]), v2) <= TOL["adam"]
+    pl = st.placement_next.long()
+    n1 = 2 * c.f * c.d
+    for q0 in range(0, c.S_tot, 32):
+        qs = slice(q0, min(q0 + 32, c.S_tot))
+        slots = torch.cat([st.W1s[qs].reshape(-1, n1), st.W2s[qs].reshape(-1, c.d * c.f)], 1)[:, lo:lo + per]
+        assert torch.equal(slots, st.master[pl[qs]].to(st.W1s.dtype))
+    print("[fullsize] adam + slots ok", flush=True)
