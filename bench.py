@@ -56,6 +56,30 @@ def kernel_work(c, w, nonempty_slots):
     }
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` as measured with rocprofv3 --pmc
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); the figures and the
+    commands that produced them are kept in profiles/hbm_traffic.json.  None if absent."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh)[workload][kernel]["bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+def calibrate_copy():
+    """A plain copy of known size, to scale the HBM counters: 8 copies of 1 GiB."""
+    import torch
+    n = 1 << 29
+    src = torch.ones(n, dtype=torch.bfloat16, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(8):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_read": 2 * n, "copy_bytes_written": 2 * n, "copies": 8}))
+
+
 def run_gpu(args):
     import torch
     import paper_2504_19925_amd as symi
@@ -140,7 +164,7 @@ def run_gpu(args):
     else:
         roof = {"bound": "hbm", "achieved": round(by / avg_s / 1e9, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(by / avg_s / 1e9 / HBM_PEAK_GBS, 4)}
-    roof.update({"kernel": dom, "avg_us": round(avg_s * 1e6, 2), "traffic": None,
+    roof.update({"kernel": dom, "avg_us": round(avg_s * 1e6, 2), "traffic": measured_traffic(c.name, dom),
                  "algorithmic_bytes": by, "algorithmic_flops": fl})
 
     out = {
@@ -174,8 +198,8 @@ def cpu_baseline(c, seconds_hint=20.0):
     except Exception:
         cores = os.cpu_count() or 1
 
-    Ts = min(c.T, 1024)                      # tokens of the sample (all E classes, full d, f)
-    Es = min(c.E, 8)                         # classes whose shard the sampled Adam step covers
+    Ts = min(c.T, 4096)                      # tokens of the sample (all E classes, full d, f)
+    Es = min(c.E, 16)                        # classes whose shard the sampled Adam step covers
     X = wl.make_tokens(c, 0, "cpu")[:Ts].float().numpy()
     z = wl.make_logits(c, 0, "cpu")[:Ts].numpy() if not c.router_matmul else \
         wl.make_logits(c, 0, "cpu", tokens=wl.make_tokens(c, 0, "cpu"))[:Ts].numpy()
@@ -218,7 +242,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a 1 GiB device copy (reference for the HBM traffic counters)")
     args = ap.parse_args()
+    if args.calibrate_copy:
+        calibrate_copy()
+        return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share of the path; --gpus must be 1 "
               "(no collectives are part of it)", file=sys.stderr)
