@@ -16,7 +16,7 @@
 // two slots.  The last two have a variable reduction length (the rows of a class).
 //
 // The MFMA is issued with the weight tile as its first operand, so a lane ends up with 4
-// consecutive output columns of one output row and writes them with one vector store.
+// consecutive output columns of one output row; a half-wave swap widens that to 8.
 #include <type_traits>
 
 #include "common.h"
@@ -325,52 +325,91 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   }
   wait_vmcnt0();   // the dummy loads of the last step
 
-  // ---- epilogue: lane owns output row (lane%32) and 4 consecutive columns per r/4
-  const int colq = (lane >> 5) * 4;
+  // ---- epilogue.  After the MFMA a lane owns one output row (lane%32) and, per 8-column
+  // group g, the 4 columns 8g + 4*(lane/32) ..; the two half-waves hold the two halves of
+  // every group.  One v_permlane32_swap per register lets the lower half-wave collect all
+  // 8 columns of the even groups and the upper half-wave those of the odd groups, so every
+  // store is 16 bytes (bf16) or 32 bytes (fp32) of one row.
+  const int hw = lane >> 5;
+  auto swap2 = [&](unsigned& a, unsigned& b) {   // a: even group, b: odd group (see above)
+    const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+    a = r[0];
+    b = r[1];
+  };
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = row0 + wm * 128 + i * 32 + (lane & 31);
-    if (row >= row1) continue;
-    if (MODE == FWD1) {
-      uint16_t* UVo = static_cast<uint16_t*>(p.UVout);
-      uint16_t* Ho = static_cast<uint16_t*>(p.H);
+    if (row < row1) {
+      if (MODE == FWD1) {
+        uint16_t* UVo = static_cast<uint16_t*>(p.UVout);
+        uint16_t* Ho = static_cast<uint16_t*>(p.H);
 #pragma unroll
-      for (int hb = 0; hb < 2; ++hb)
+        for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int hu = n0 + wn * 64 + hb * 32 + g * 8 + colq;
-          if (hu >= p.f) continue;
-          float u[4], v[4], h[4];
+          for (int ge = 0; ge < 4; ge += 2) {
+            unsigned pu[2][2], pv[2][2], ph[2][2];   // [even/odd group][column pair]
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            u[c] = acc[i][2 * hb][g * 4 + c];
-            v[c] = acc[i][2 * hb + 1][g * 4 + c];
-            h[c] = u[c] * sigmoid_fast(u[c]) * v[c];
+            for (int o = 0; o < 2; ++o)
+#pragma unroll
+              for (int c2 = 0; c2 < 2; ++c2) {
+                const int r = (ge + o) * 4 + 2 * c2;
+                const float u0 = acc[i][2 * hb][r], u1 = acc[i][2 * hb][r + 1];
+                const float v0 = acc[i][2 * hb + 1][r], v1 = acc[i][2 * hb + 1][r + 1];
+                pu[o][c2] = pack_bf16x2(u0, u1);
+                pv[o][c2] = pack_bf16x2(v0, v1);
+                ph[o][c2] = pack_bf16x2(u0 * sigmoid_fast(u0) * v0, u1 * sigmoid_fast(u1) * v1);
+              }
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2) {
+              swap2(pu[0][c2], pu[1][c2]);
+              swap2(pv[0][c2], pv[1][c2]);
+              swap2(ph[0][c2], ph[1][c2]);
+            }
+            const int hu = n0 + wn * 64 + hb * 32 + (ge + hw) * 8;
+            if (hu < p.f) {
+              const long long o = (long long)row * 2 * p.f + hu;
+              *reinterpret_cast<uint4*>(UVo + o) = make_uint4(pu[0][0], pu[0][1], pu[1][0], pu[1][1]);
+              *reinterpret_cast<uint4*>(UVo + o + p.f) = make_uint4(pv[0][0], pv[0][1], pv[1][0], pv[1][1]);
+              *reinterpret_cast<uint4*>(Ho + (long long)row * p.f + hu) =
+                  make_uint4(ph[0][0], ph[0][1], ph[1][0], ph[1][1]);
+            }
           }
-          const long long o = (long long)row * 2 * p.f + hu;
-          *reinterpret_cast<uint2*>(UVo + o) = make_uint2(pack_bf16x2(u[0], u[1]), pack_bf16x2(u[2], u[3]));
-          *reinterpret_cast<uint2*>(UVo + o + p.f) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-          *reinterpret_cast<uint2*>(Ho + (long long)row * p.f + hu) =
-              make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
-        }
-    } else {
+      } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col = n0 + wn * 128 + j * 32 + g * 8 + colq;
-          if (col >= p.N) continue;
-          const float x0 = acc[i][j][g * 4], x1 = acc[i][j][g * 4 + 1], x2 = acc[i][j][g * 4 + 2],
-                      x3 = acc[i][j][g * 4 + 3];
-          if (MODE == FWD2 || MODE == BWD_DX || MODE == BWD_DH) {
-            uint16_t* Co = static_cast<uint16_t*>(p.C);
-            *reinterpret_cast<uint2*>(Co + (long long)row * p.N + col) =
-                make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
-          } else {  // weight gradients, fp32
-            float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride;
-            *reinterpret_cast<float4*>(Co + (long long)row * p.N + col) = make_float4(x0, x1, x2, x3);
+          for (int ge = 0; ge < 4; ge += 2) {
+            const int col = n0 + wn * 128 + j * 32 + (ge + hw) * 8;
+            if (MODE == FWD2 || MODE == BWD_DX || MODE == BWD_DH) {
+              unsigned px[2][2];
+#pragma unroll
+              for (int o = 0; o < 2; ++o)
+#pragma unroll
+                for (int c2 = 0; c2 < 2; ++c2)
+                  px[o][c2] = pack_bf16x2(acc[i][j][(ge + o) * 4 + 2 * c2], acc[i][j][(ge + o) * 4 + 2 * c2 + 1]);
+              swap2(px[0][0], px[1][0]);
+              swap2(px[0][1], px[1][1]);
+              if (col < p.N) {
+                uint16_t* Co = static_cast<uint16_t*>(p.C);
+                *reinterpret_cast<uint4*>(Co + (long long)row * p.N + col) =
+                    make_uint4(px[0][0], px[0][1], px[1][0], px[1][1]);
+              }
+            } else {  // weight gradients, fp32
+              unsigned xe[4], xo[4];
+#pragma unroll
+              for (int c = 0; c < 4; ++c) {
+                xe[c] = __float_as_uint(acc[i][j][ge * 4 + c]);
+                xo[c] = __float_as_uint(acc[i][j][(ge + 1) * 4 + c]);
+                swap2(xe[c], xo[c]);
+              }
+              if (col < p.N) {
+                float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride + (long long)row * p.N + col;
+                *reinterpret_cast<uint4*>(Co) = make_uint4(xe[0], xe[1], xe[2], xe[3]);
+                *reinterpret_cast<uint4*>(Co + 4) = make_uint4(xo[0], xo[1], xo[2], xo[3]);
+              }
+            }
           }
-        }
+      }
     }
     __builtin_amdgcn_sched_barrier(0);   // one 32-row block at a time: bounds the registers in flight
   }

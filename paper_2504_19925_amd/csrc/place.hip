@@ -8,8 +8,8 @@
 // one replica is shrunk next, so both versions here pick "first maximum among classes
 // with more than one replica" directly: identical counts in at most E steps.
 //
-// Device version: one 64-lane wavefront; lane l owns classes l, l+64, ...; the arg-max /
-// arg-min is a strided scan followed by a butterfly over (D, index) pairs.  It runs on
+// Device version: one 64-lane wavefront; lane l keeps classes l, l+64, ... in registers and
+// the correction loops are evaluated in closed form (see place_kernel).  It runs on
 // the stream between the histogram and the optimizer step, so no host round trip is
 // needed to learn the next placement.
 #include <vector>
@@ -25,79 +25,129 @@ __device__ __forceinline__ long long wave_sum_ll(long long x) {
   return x;
 }
 
+__device__ __forceinline__ int wave_sum_i(int x) {
+  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+  return x;
+}
+
+// NPL = classes per lane (class lane + 64*i lives in register i of its lane).
+//
+// The two correction loops of the algorithm are evaluated in closed form.  Shrinking: a
+// class with more than one replica starts with diff in (-1, 0]; each removal lowers its
+// diff by exactly 1, below every class not yet visited in the same round.  The loop
+// therefore proceeds in rounds over the classes in (diff descending, index ascending)
+// order, a class dropping out once it is down to one replica.  With X replicas to remove,
+// R = the largest number of full rounds with sum_i min(counts_i - 1, R) <= X, and the
+// remaining X - that sum removals go to the first classes of that order still holding
+// more than one replica.  Growing: the deficit Y is smaller than the number of classes
+// that were not lifted to one replica, so the Y classes with the smallest (diff, index)
+// get one replica each.
+template <int NPL>
 __global__ __launch_bounds__(64) void place_kernel(const int32_t* __restrict__ pop,
                                                    int32_t* __restrict__ counts,
                                                    int32_t* __restrict__ placement,
                                                    int32_t* __restrict__ first_slot, int E, int S) {
-  __shared__ long long D[PLACE_MAX_E];
-  __shared__ int cnt[PLACE_MAX_E];
+  __shared__ long long Dl[PLACE_MAX_E];
+  __shared__ int cl[PLACE_MAX_E];
   __shared__ int first[PLACE_MAX_E + 1];
   const int lane = threadIdx.x;
 
+  long long p[NPL];
   long long psum = 0;
-  for (int i = lane; i < E; i += 64) psum += pop[i] > 0 ? pop[i] : 0;
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    const int c = lane + 64 * i;
+    p[i] = (c < E && pop[c] > 0) ? pop[c] : 0;
+    psum += p[i];
+  }
   psum = wave_sum_ll(psum);
   const bool uniform = psum == 0;  // no popularity recorded yet: treat all classes alike
   const long long P = uniform ? E : psum;
 
-  long long tot = 0;
-  for (int i = lane; i < E; i += 64) {
-    const long long p = uniform ? 1 : (pop[i] > 0 ? pop[i] : 0);
-    long long c = p * S / P;  // floor(goal)
-    if (c < 1) c = 1;         // every class stays reachable
-    cnt[i] = (int)c;
-    D[i] = c * P - p * S;
-    tot += c;
+  long long D[NPL];
+  int cnt[NPL];
+  int tot = 0;
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    const int c = lane + 64 * i;
+    const long long pi = uniform ? 1 : p[i];
+    long long k = pi * S / P;  // floor(goal)
+    if (k < 1) k = 1;          // every class stays reachable
+    cnt[i] = c < E ? (int)k : 0;
+    D[i] = k * P - pi * S;
+    tot += cnt[i];
   }
-  long long total = wave_sum_ll(tot);
-  __syncthreads();
+  const int total = wave_sum_i(tot);
 
-  // too many replicas: shrink the class whose count exceeds its goal the most
-  for (int it = 0; total > S && it < E + S; ++it) {
-    long long bd = 0;
-    int bi = INT32_MAX;
-    for (int i = lane; i < E; i += 64)
-      if (cnt[i] > 1 && (bi == INT32_MAX || D[i] > bd)) { bd = D[i]; bi = i; }
-    for (int m = 32; m >= 1; m >>= 1) {
-      const long long od = __shfl_xor(bd, m, 64);
-      const int oi = __shfl_xor(bi, m, 64);
-      if (oi != INT32_MAX && (bi == INT32_MAX || od > bd || (od == bd && oi < bi))) { bd = od; bi = oi; }
+  if (total > S) {
+    const int X = total - S;
+    int lo = 0, hi = S;       // full rounds
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      int f = 0;
+#pragma unroll
+      for (int i = 0; i < NPL; ++i) f += min(max(cnt[i] - 1, 0), mid);
+      if (wave_sum_i(f) <= X) lo = mid; else hi = mid - 1;
     }
-    if (bi == INT32_MAX) break;
-    if (lane == 0) { cnt[bi] -= 1; D[bi] -= P; }
-    total -= 1;
-    __syncthreads();
-  }
-  // too few: grow the class that lags its goal the most
-  for (int it = 0; total < S && it < E + S; ++it) {
-    long long bd = 0;
-    int bi = INT32_MAX;
-    for (int i = lane; i < E; i += 64)
-      if (bi == INT32_MAX || D[i] < bd) { bd = D[i]; bi = i; }
-    for (int m = 32; m >= 1; m >>= 1) {
-      const long long od = __shfl_xor(bd, m, 64);
-      const int oi = __shfl_xor(bi, m, 64);
-      if (oi != INT32_MAX && (bi == INT32_MAX || od < bd || (od == bd && oi < bi))) { bd = od; bi = oi; }
+    const int R = lo;
+    int f = 0;
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      const int dec = min(max(cnt[i] - 1, 0), R);
+      cnt[i] -= dec;
+      f += dec;
     }
-    if (lane == 0) { cnt[bi] += 1; D[bi] += P; }
-    total += 1;
+    const int rem = X - wave_sum_i(f);
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      const int c = lane + 64 * i;
+      if (c < E) { Dl[c] = D[i]; cl[c] = cnt[i]; }
+    }
     __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      const int c = lane + 64 * i;
+      if (c < E && cnt[i] > 1 && rem > 0) {
+        int rank = 0;   // classes still shrinkable that come earlier in (diff desc, index asc)
+        for (int j = 0; j < E; ++j)
+          rank += (cl[j] > 1 && (Dl[j] > D[i] || (Dl[j] == D[i] && j < c))) ? 1 : 0;
+        if (rank < rem) cnt[i] -= 1;
+      }
+    }
+  } else if (total < S) {
+    const int Y = S - total;
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      const int c = lane + 64 * i;
+      if (c < E) Dl[c] = D[i];
+    }
+    __syncthreads();
+    const int full = Y / E, rem = Y % E;   // full is 0 for any popularity; kept for safety
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      const int c = lane + 64 * i;
+      if (c < E) {
+        int rank = 0;   // classes that come earlier in (diff asc, index asc)
+        for (int j = 0; j < E; ++j) rank += (Dl[j] < D[i] || (Dl[j] == D[i] && j < c)) ? 1 : 0;
+        cnt[i] += full + (rank < rem ? 1 : 0);
+      }
+    }
   }
 
   // first_slot = exclusive prefix sum of counts, 64 classes per step
   int carry = 0;
-  for (int base = 0; base < E; base += 64) {
-    const int i = base + lane;
-    const int c = i < E ? cnt[i] : 0;
-    int incl = c;
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    const int c = lane + 64 * i;
+    int incl = cnt[i];
     for (int o = 1; o < 64; o <<= 1) {
       const int up = __shfl_up(incl, o, 64);
       if (lane >= o) incl += up;
     }
-    if (i < E) {
-      first[i] = carry + incl - c;
-      first_slot[i] = carry + incl - c;
-      counts[i] = c;
+    if (c < E) {
+      first[c] = carry + incl - cnt[i];
+      first_slot[c] = carry + incl - cnt[i];
+      counts[c] = cnt[i];
     }
     carry += __shfl(incl, 63, 64);
   }
@@ -159,8 +209,15 @@ extern "C" int symi_place(const symi_cfg* cfg, const int32_t* popularity, int32_
   if (int rc = check_cfg(cfg, "symi_place")) return rc;
   SYMI_REQUIRE(popularity && counts && placement && first_slot, "symi_place", "NULL pointer");
   hipStream_t st = as_stream(stream);
-  SYMI_TIMED(K_PLACE, st, (place_kernel<<<1, 64, 0, st>>>(popularity, counts, placement, first_slot,
-                                                        cfg->E, cfg->S_tot)));
+  const int E = cfg->E, S = cfg->S_tot;
+  if (E <= 64)
+    SYMI_TIMED(K_PLACE, st, (place_kernel<1><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
+  else if (E <= 128)
+    SYMI_TIMED(K_PLACE, st, (place_kernel<2><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
+  else if (E <= 256)
+    SYMI_TIMED(K_PLACE, st, (place_kernel<4><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
+  else
+    SYMI_TIMED(K_PLACE, st, (place_kernel<16><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
   SYMI_LAUNCH_CHECK("symi_place");
   return SYMI_OK;
 }

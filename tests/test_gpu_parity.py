@@ -182,3 +182,35 @@ def test_adam_weight_decay_grad_scale_and_later_steps():
         check_iteration(st, X, logits, dY, hp_kw=dict(step=it + 1, weight_decay=0.05,
                                                       grad_scale=0.125, lr=3e-3))
         st.hist_prev.copy_(st.hist)
+
+
+def test_place_device_matches_oracle_on_random_popularities():
+    """The device scheduler evaluates Algorithm 1's correction loops in closed form; it must
+    reproduce the literal loops (the oracle) bit for bit, also on adversarial ties."""
+    import random
+    import paper_2504_19925_amd as symi
+    rnd = random.Random(99)
+    cases = [([5, 5, 4, 2], 16), ([1024, 1024, 0, 0, 0, 0, 0, 0], 16), ([0] * 64, 96), ([10, 3, 10, 5], 16),
+             ([1000000] + [0] * 63, 64), ([7] * 16, 64), ([1] * 130, 257), ([3, 3, 3], 64)]
+    for _ in range(400):
+        E = rnd.choice([1, 2, 3, 8, 24, 64, 65, 128, 130, 300, 1024])
+        S = rnd.randint(E, min(4096, 4 * E + 3))
+        kind = rnd.random()
+        if kind < 0.3:
+            pop = [rnd.choice([0, 0, 1, 2, 2, 7]) for _ in range(E)]           # many ties
+        elif kind < 0.6:
+            pop = [int(100000 / (r + 1) ** 1.2) for r in range(E)]
+            rnd.shuffle(pop)
+        else:
+            pop = [rnd.choice([0, 1, rnd.randint(0, 60000)]) for _ in range(E)]
+        cases.append((pop, S))
+    for pop, S in cases:
+        E = len(pop)
+        cfg = symi.SymiCfg.make(64, E, 1, 128, 256, S, 1, 0, "f32", 1)
+        dev = dict(dtype=torch.int32, device="cuda")
+        counts, placement, first = torch.zeros(E, **dev), torch.zeros(S, **dev), torch.zeros(E + 1, **dev)
+        symi.symi_place(cfg, torch.tensor(pop, **dev), counts, placement, first)
+        oc, op, of = O.place(pop, S)
+        assert counts.cpu().tolist() == oc.tolist(), (pop[:16], S)
+        assert placement.cpu().tolist() == op.tolist()
+        assert first.cpu().tolist() == of.tolist()
