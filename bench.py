@@ -198,8 +198,8 @@ def cpu_baseline(c, seconds_hint=20.0):
     except Exception:
         cores = os.cpu_count() or 1
 
-    Ts = min(c.T, 4096)                      # tokens of the sample (all E classes, full d, f)
-    Es = min(c.E, 16)                        # classes whose shard the sampled Adam step covers
+    Ts = min(c.T, 8192)                      # tokens of the sample (all E classes, full d, f)
+    Es = min(c.E, 64)                        # classes whose shard the sampled Adam step covers
     X = wl.make_tokens(c, 0, "cpu")[:Ts].float().numpy()
     z = wl.make_logits(c, 0, "cpu")[:Ts].numpy() if not c.router_matmul else \
         wl.make_logits(c, 0, "cpu", tokens=wl.make_tokens(c, 0, "cpu"))[:Ts].numpy()
