@@ -112,13 +112,39 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
 
 __device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+template <int V> struct IC { static constexpr int value = V; };
+
+// LDS reads with an immediate byte offset; nothing waits for them (see the kernel)
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+// transposing read: 4 k-values of one column per 8-byte half; the second half sits 4 k-rows
+// (2048 bytes) further
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_tr(unsigned addr) {
+  shortx4 lo, hi;
+  asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+               : "=&v"(lo), "=&v"(hi) : "v"(addr), "n"(OFF), "n"(OFF + 2048));
+  union { shortx4 h[2]; bf16x8 v; } u;
+  u.h[0] = lo;
+  u.h[1] = hi;
+  return u.v;
+}
+
 template <int MODE>
 __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
-  __shared__ __attribute__((aligned(1024))) uint16_t sA0[BM * BK];
-  __shared__ __attribute__((aligned(1024))) uint16_t sB0[BN * BK];
-  __shared__ __attribute__((aligned(1024))) uint16_t sA1[BM * BK];
-  __shared__ __attribute__((aligned(1024))) uint16_t sB1[BN * BK];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // [left stage 0 | left stage 1 | right stage 0 | right stage 1], 32 KB each: the two
+  // stages of an operand differ by an immediate offset of the LDS read instructions
+  __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * BM * BK + 2 * BN * BK];
+  uint16_t* const sA0 = smem;
+  uint16_t* const sA1 = smem + BM * BK;
+  uint16_t* const sB0 = smem + 2 * BM * BK;
+  uint16_t* const sB1 = smem + 2 * BM * BK + BN * BK;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, and known to be
   const int wm = wave >> 1, wn = wave & 1;
   constexpr bool VARM = MODE <= BWD_DX;
   constexpr bool A_KC = VARM;                       // left operand reduction-contiguous
@@ -163,18 +189,18 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
                         : MODE == BWD_DX ? p.d : MODE == WGRAD2 ? p.f : p.d;
   const uint16_t* zero = g_zero_chunk;
 
-  // ---- direct-to-LDS loads: a wave-uniform base per reduction step plus 32-bit per-lane
-  // element offsets, one per instruction j (0..7) and operand.
+  // ---- direct-to-LDS loads: a wave-uniform base per reduction step plus a 32-bit per-lane
+  // element offset, one per instruction j (0..7) and operand.
   // reduction-contiguous tile: wavefront w, instruction j fills tile rows w*64 + 8j .. +8;
   //   lane -> (row + lane/8, physical chunk lane%8)
   // reduction-strided tile: wavefront w, instruction j fills k-rows w*16 + 2j, +1;
   //   lane -> (k-row + lane/32, physical chunk lane%32)
   // Rows / column chunks beyond the operand's extent are clamped to a valid one: what
-  // they bring in only reaches outputs that are never stored.  Reduction indices beyond
-  // K (only in the last, partial step) load zeros instead.
-  // Source offsets are recomputed from four lane constants at every load (a handful of
-  // VALU ops against 4 MFMAs) instead of being kept in registers: the accumulators and
-  // fragments leave no room for 16 precomputed addresses.
+  // they bring in only reaches outputs that are never stored.
+  // The main loop takes its 16 offsets from registers (no vector arithmetic next to the
+  // MFMAs).  The last iterations, which load the partial step or steps beyond K, recompute
+  // them from five lane constants and point every reduction index beyond K at a block of
+  // zeros.
   int kc_row = wave * 64 + (lane >> 3);                        // tile row of instruction 0
   int kc_c0 = (lane & 7) ^ ((lane >> 4) & 7);                  // logical chunk for even j
   int ks_kb = wave * 16 + (lane >> 5);                         // k-row of instruction 0
@@ -201,74 +227,97 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   // LDS destination of instruction j (wave-uniform): both layouts advance 1 KB per j
   const int wdst = wave * 8 * 512;  // elements: 8 instructions x 512 elements per wavefront
   // q = 0..15: even = left operand, odd = right operand, instruction j = q/2
-  auto dma_one = [&](uint16_t* sA, uint16_t* sB, int k0, int q, auto tail) {
+  // offset of this lane's 16 bytes for instruction j, and its reduction index within the step
+  auto lane_off = [&](bool right, int j, int& krel) -> unsigned {
+    const bool kcontig = right ? B_KC : A_KC;
+    const int ld = (int)(right ? ldb : lda);
+    const int lim = right ? b_lim : a_lim;
+    if (kcontig) {
+      const int kc = kc_c0 ^ (4 * (j & 1));
+      krel = kc * 8;
+      if (right && MODE == FWD1) {
+        // tile row t -> hidden unit n0 + (t>>7)*64 + ((t>>6)&1)*32 + (t&31), up half if (t>>5)&1
+        const int hu = min(n0 + f1_row + 8 * (j & 3), lim);
+        return (unsigned)(((j >> 2) * p.f + hu) * ld + kc * 8);
+      }
+      return (unsigned)(min(kc_row + 8 * j, lim) * ld + kc * 8);
+    }
+    const int c = ks_c0 ^ (4 * (j & 1));
+    krel = ks_kb + 2 * j;
+    return (unsigned)((ks_kb + 2 * j) * ld + (c * 8 < lim ? c : 0) * 8);
+  };
+  unsigned voA[8], voB[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    int unused;
+    voA[j] = lane_off(false, j, unused);
+    voB[j] = lane_off(true, j, unused);
+  }
+  // q = 0..15: even = left operand, odd = right operand, instruction j = q/2
+  auto dma_one = [&](uint16_t* sA, uint16_t* sB, int k0, int q, auto partial) {
     const int j = q >> 1;
     const bool right = q & 1;
     const bool kcontig = right ? B_KC : A_KC;
     const uint16_t* base = right ? b_base : a_base;
-    const int ld = (int)(right ? ldb : lda);
-    const int lim = right ? b_lim : a_lim;
-    unsigned off;
-    int kidx;
-    if (kcontig) {
-      const int kc = kc_c0 ^ (4 * (j & 1));
-      kidx = k0 + kc * 8;
-      if (right && MODE == FWD1) {
-        // tile row t -> hidden unit n0 + (t>>7)*64 + ((t>>6)&1)*32 + (t&31), up half if (t>>5)&1
-        const int hu = min(n0 + f1_row + 8 * (j & 3), lim);
-        off = (unsigned)(((j >> 2) * p.f + hu) * ld + kc * 8);
-      } else {
-        off = (unsigned)(min(kc_row + 8 * j, lim) * ld + kc * 8);
-      }
+    const long long ld = right ? ldb : lda;
+    const uint16_t* sbase = kcontig ? base + k0 : base + (long long)k0 * ld;   // wave-uniform
+    const uint16_t* src;
+    if (decltype(partial)::value) {
+      int krel;
+      const unsigned off = lane_off(right, j, krel);
+      src = k0 + krel < K ? sbase + (size_t)off : zero;
     } else {
-      const int c = ks_c0 ^ (4 * (j & 1));
-      kidx = k0 + ks_kb + 2 * j;
-      off = (unsigned)((ks_kb + 2 * j) * ld + (c * 8 < lim ? c : 0) * 8);
-    }
-    const uint16_t* src = (kcontig ? base + k0 : base + (long long)k0 * ld) + (size_t)off;
-    if (decltype(tail)::value) {
-      if (kidx >= K) src = zero;
+      src = sbase + (size_t)(right ? voB[j] : voA[j]);
     }
     __builtin_amdgcn_global_load_lds(SYMI_GPTR(src), SYMI_LPTR((right ? sB : sA) + wdst + j * 512), 16, 0, 0);
   };
-
-  // ---- fragment addresses (element offsets inside a stage)
-  // KC: row (sub*32 + lane%32), chunk (2*ks + lane/32) ^ ((lane%32 >> 1) & 7)
-  const int r31 = lane & 31;
-  int kc_off[4];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) kc_off[ks] = r31 * BK + (((2 * ks + (lane >> 5)) ^ ((r31 >> 1) & 7)) * 8);
+  // ---- fragment reads.  Byte address of this lane's piece inside stage 0 of its operand,
+  // everything else (32-row block, 16-deep sub-step, stage) is an immediate offset.
+  // KC: row (sub*32 + lane%32), chunk (2*ks + lane/32) ^ ((lane%32 >> 1) & 7); the xor makes the
+  //   sub-step a per-lane quantity, so there is one address per sub-step.
   // KS: lane = 16*g + jj supplies the address of k-row (16*ks + 8*(g>>1) + 4*e + jj/4),
-  // 8-byte piece (jj%4) of columns sub*32 + 16*(g&1) ..; it receives column sub*32 + lane%32
+  //   8-byte piece (jj%4) of columns sub*32 + 16*(g&1) ..; it receives column sub*32 + lane%32;
+  //   one address per 32-column block, the sub-step is an immediate (16 k-rows of 512 B).
+  const int r31 = lane & 31;
   const int g4 = lane >> 4, jj = lane & 15;
   const int ks_h2 = (10 * ((jj >> 2) & 1)) ^ (4 * ((jj >> 3) & 1));   // swizzle of this lane's k-row
   const int ks_row = (8 * (g4 >> 1) + (jj >> 2)) * 256;
-  int ks_col[4];
+  unsigned adA[4], adB[4];
 #pragma unroll
-  for (int sub = 0; sub < 4; ++sub)
-    ks_col[sub] = (((4 * sub + 2 * (g4 & 1) + ((jj & 3) >> 1)) ^ ks_h2) * 8) + 4 * (jj & 1);
-
-  // The transposing reads are issued as inline assembly: the compiler would otherwise
-  // order every such read after all direct-to-LDS loads in flight (it cannot tell the two
-  // stages apart) and stall on the prefetch it was meant to overlap.  Their completion is
-  // awaited by hand (lgkmcnt(0)) before the MFMAs that consume them.
-  auto frag = [&](const uint16_t* tile, bool kc, int wbase_rows, int sub, int ks) -> bf16x8 {
-    if (kc) {
-      return *reinterpret_cast<const bf16x8*>(tile + (wbase_rows + sub * 32) * BK + kc_off[ks]);
+  for (int x = 0; x < 4; ++x) {
+    const int kc = r31 * BK + (((2 * x + (lane >> 5)) ^ ((r31 >> 1) & 7)) * 8);             // x = sub-step
+    const int ksc = ks_row + (((4 * x + 2 * (g4 & 1) + ((jj & 3) >> 1)) ^ ks_h2) * 8) + 4 * (jj & 1);  // x = block
+    adA[x] = (unsigned)(size_t)SYMI_LPTR(sA0) + 2u * (unsigned)(A_KC ? wm * 128 * BK + kc : wm * 128 + ksc);
+    adB[x] = (unsigned)(size_t)SYMI_LPTR(sB0) + 2u * (unsigned)(B_KC ? wn * 128 * BK + kc : wn * 128 + ksc);
+  }
+  // All LDS reads are inline assembly: the compiler cannot tell the stage being read from the
+  // one being filled by direct-to-LDS loads and would wait for the prefetch before every
+  // read.  Completion is awaited by hand (lgkmcnt(0)) at the start of the phase that uses them.
+  bf16x8 fa[2][4], fb[2][4];   // two register sets: one feeds the MFMAs, the other is being filled
+  auto load_frags = [&](auto bufc, auto stagec, auto ksc) {
+    constexpr int bu = decltype(bufc)::value, S = decltype(stagec)::value, KS = decltype(ksc)::value;
+    constexpr int SO = S * BM * BK * 2;   // stage offset in bytes
+    if (A_KC) {
+      fa[bu][0] = lds_read_b128<SO + 0 * 4096>(adA[KS]);
+      fa[bu][1] = lds_read_b128<SO + 1 * 4096>(adA[KS]);
+      fa[bu][2] = lds_read_b128<SO + 2 * 4096>(adA[KS]);
+      fa[bu][3] = lds_read_b128<SO + 3 * 4096>(adA[KS]);
     } else {
-      const unsigned addr =
-          (unsigned)(size_t)SYMI_LPTR(tile) + 2u * (unsigned)(ks_row + wbase_rows + ks_col[sub]);
-      shortx4 lo, hi;
-      switch (ks) {   // the k-step is an immediate offset: 16 k-rows of 512 bytes
-        case 0: asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:2048" : "=&v"(lo), "=&v"(hi) : "v"(addr)); break;
-        case 1: asm volatile("ds_read_b64_tr_b16 %0, %2 offset:8192\n\tds_read_b64_tr_b16 %1, %2 offset:10240" : "=&v"(lo), "=&v"(hi) : "v"(addr)); break;
-        case 2: asm volatile("ds_read_b64_tr_b16 %0, %2 offset:16384\n\tds_read_b64_tr_b16 %1, %2 offset:18432" : "=&v"(lo), "=&v"(hi) : "v"(addr)); break;
-        default: asm volatile("ds_read_b64_tr_b16 %0, %2 offset:24576\n\tds_read_b64_tr_b16 %1, %2 offset:26624" : "=&v"(lo), "=&v"(hi) : "v"(addr)); break;
-      }
-      union { shortx4 h[2]; bf16x8 v; } u;
-      u.h[0] = lo;
-      u.h[1] = hi;
-      return u.v;
+      fa[bu][0] = lds_read_tr<SO + KS * 8192>(adA[0]);
+      fa[bu][1] = lds_read_tr<SO + KS * 8192>(adA[1]);
+      fa[bu][2] = lds_read_tr<SO + KS * 8192>(adA[2]);
+      fa[bu][3] = lds_read_tr<SO + KS * 8192>(adA[3]);
+    }
+    if (B_KC) {
+      fb[bu][0] = lds_read_b128<SO + 0 * 4096>(adB[KS]);
+      fb[bu][1] = lds_read_b128<SO + 1 * 4096>(adB[KS]);
+      fb[bu][2] = lds_read_b128<SO + 2 * 4096>(adB[KS]);
+      fb[bu][3] = lds_read_b128<SO + 3 * 4096>(adB[KS]);
+    } else {
+      fb[bu][0] = lds_read_tr<SO + KS * 8192>(adB[0]);
+      fb[bu][1] = lds_read_tr<SO + KS * 8192>(adB[1]);
+      fb[bu][2] = lds_read_tr<SO + KS * 8192>(adB[2]);
+      fb[bu][3] = lds_read_tr<SO + KS * 8192>(adB[3]);
     }
   };
 
@@ -280,50 +329,85 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // ---- main loop.  A reduction step (64 deep, stage S = step & 1) is four phases of 16
+  // MFMAs.  Phase ks consumes register set ks & 1 while the fragments of the next phase are
+  // read into the other set.  Phase 3 first waits for the loads of the next step, meets the
+  // other wavefronts (after which nobody reads stage S any more: its last fragments already
+  // sit in registers), reads the first fragments of the other stage and starts loading step
+  // + 2 into stage S; phase 0 of the next step issues the second half of those loads.  A
+  // load therefore has three to four phases to arrive, and neither an LDS round trip nor a
+  // load latency is exposed to the MFMA pipe.  Steps beyond the last one load zeros (dummy
+  // loads keep the loop free of branches, which is what lets the 256 accumulators stay put).
   const int nk = (K + BK - 1) / BK;
-  // computes stage (At, Bt) while reduction step `next` is loaded into (nA, nB); beyond
-  // the last step every lane loads zeros (a dummy that keeps the loop free of branches,
-  // which is what lets the 256 accumulators stay put in their registers)
-  auto tile_step = [&](const uint16_t* At, const uint16_t* Bt, uint16_t* nA, uint16_t* nB, int next) {
-    // keep the address arithmetic of the loads inside the step (see dma_one)
-    asm volatile("" : "+v"(kc_row), "+v"(kc_c0), "+v"(ks_kb), "+v"(ks_c0), "+v"(f1_row));
+  auto phase = [&](auto ksc, auto stagec, int step, auto partial) {
+    constexpr int KS = decltype(ksc)::value, S = decltype(stagec)::value;
+    constexpr int bu = KS & 1;
+    uint16_t* const cA = S ? sA1 : sA0;
+    uint16_t* const cB = S ? sB1 : sB0;
+    uint16_t* const oA = S ? sA0 : sA1;
+    uint16_t* const oB = S ? sB0 : sB1;
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): the fragments of this phase
+    if (KS == 3) {
+      wait_vmcnt0();                      // my share of the next step has landed
+      __builtin_amdgcn_s_barrier();       // ... so has everybody's, and stage S is free
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (KS == 3) load_frags(IC<bu ^ 1>{}, IC<S ^ 1>{}, IC<0>{});
+    else load_frags(IC<bu ^ 1>{}, IC<S>{}, IC<(KS + 1) & 3>{});
+    __builtin_amdgcn_sched_barrier(0);
+    if (decltype(partial)::value && (KS == 3 || KS == 0)) {
+      // keep the address arithmetic of these loads inside the phase (not hoisted into registers)
+      asm volatile("" : "+v"(kc_row), "+v"(kc_c0), "+v"(ks_kb), "+v"(ks_c0), "+v"(f1_row));
+    }
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[4], bfr[4];
+    for (int i = 0; i < 4; ++i) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        af[i] = frag(At, A_KC, wm * 128, i, ks);
-        bfr[i] = frag(Bt, B_KC, wn * 128, i, ks);
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[bu][j], fa[bu][i], acc[i][j], 0, 0, 0);
+      if (KS == 3) {
+        dma_one(cA, cB, (step + 2) * BK, 2 * i, partial);
+        dma_one(cA, cB, (step + 2) * BK, 2 * i + 1, partial);
+      } else if (KS == 0) {
+        dma_one(oA, oB, (step + 1) * BK, 8 + 2 * i, partial);
+        dma_one(oA, oB, (step + 1) * BK, 8 + 2 * i + 1, partial);
       }
-      if (!A_KC || !B_KC) {
-        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): the hand-issued transposing reads
-        __builtin_amdgcn_sched_barrier(0);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-        dma_one(nA, nB, next * BK, ks * 4 + i, std::true_type{});
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-  if (nk > 0) {
+  auto pair = [&](int t, auto partial) {
+    phase(IC<0>{}, IC<0>{}, t, partial);
+    phase(IC<1>{}, IC<0>{}, t, partial);
+    phase(IC<2>{}, IC<0>{}, t, partial);
+    phase(IC<3>{}, IC<0>{}, t, partial);
+    phase(IC<0>{}, IC<1>{}, t + 1, partial);
+    phase(IC<1>{}, IC<1>{}, t + 1, partial);
+    phase(IC<2>{}, IC<1>{}, t + 1, partial);
+    phase(IC<3>{}, IC<1>{}, t + 1, partial);
+  };
+  if (K >= 2 * BK) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) dma_one(sA0, sB0, 0, q, std::false_type{});
+#pragma unroll
+    for (int q = 0; q < 8; ++q) dma_one(sA1, sB1, BK, q, std::false_type{});
+  } else {
 #pragma unroll
     for (int q = 0; q < 16; ++q) dma_one(sA0, sB0, 0, q, std::true_type{});
+#pragma unroll
+    for (int q = 0; q < 8; ++q) dma_one(sA1, sB1, BK, q, std::true_type{});
   }
-  for (int t = 0; t < nk; t += 2) {
-    wait_vmcnt0();
-    __builtin_amdgcn_s_barrier();
-    tile_step(sA0, sB0, sA1, sB1, t + 1);
-    // always a pair: for an odd step count the second stage holds the zeros of the dummy
-    // load and adds nothing (a mid-loop exit would cost more than the idle step)
-    wait_vmcnt0();
-    __builtin_amdgcn_s_barrier();
-    tile_step(sA1, sB1, sA0, sB0, t + 2);
-  }
-  wait_vmcnt0();   // the dummy loads of the last step
+  __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8): step 0 has landed, the half of step 1 may still fly
+  __builtin_amdgcn_s_barrier();
+  load_frags(IC<0>{}, IC<0>{}, IC<0>{});
+  // always pairs of steps: for an odd step count the second stage holds the zeros of the
+  // dummy loads and adds nothing (a mid-loop exit would cost more than the idle step).  A
+  // pair starting at step t loads steps up to t + 3.
+  int t = 0;
+  for (; (t + 4) * BK <= K; t += 2) pair(t, std::false_type{});
+  for (; t < nk; t += 2) pair(t, std::true_type{});
+  // dummy loads and the fragment read of the last phase are still in flight: they must
+  // not outlive the workgroup's LDS allocation
+  __builtin_amdgcn_s_waitcnt(0xC07F);
+  wait_vmcnt0();
 
   // ---- epilogue.  After the MFMA a lane owns one output row (lane%32) and, per 8-column
   // group g, the 4 columns 8g + 4*(lane/32) ..; the two half-waves hold the two halves of
