@@ -58,6 +58,8 @@ WsLayout ws_layout(const symi_cfg* c) {
   off += align_up((nblk + 1) * c->E * sizeof(int32_t), 256);
   L.tile_map = off;
   off += align_up((4 + 4 * mtiles) * sizeof(int32_t), 256);
+  L.class_order = off;
+  off += align_up((size_t)c->E * sizeof(int32_t), 256);
   L.duv = off;
   off += align_up(A * 2 * c->f * w, 256);
   L.dh = off;

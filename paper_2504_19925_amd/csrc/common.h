@@ -73,6 +73,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 struct WsLayout {
   size_t blk_counts;   // dispatch: [nblk][E] i32 per-block class counts, then bases
   size_t tile_map;     // expert fwd/bwd: m-tile table, see gemm.hip
+  size_t class_order;  // expert bwd: classes by decreasing row count
   size_t duv;          // expert bwd: dUV [A,2f] in the activation dtype
   size_t dh;           // expert bwd (bf16): dh [A,f]
   size_t total;

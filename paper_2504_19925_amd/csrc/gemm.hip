@@ -44,6 +44,7 @@ struct GemmParams {
   int N;   // output columns (FWD1: f, counted once)
   int K;   // reduction length when fixed
   int d, f;
+  const int32_t* class_order;   // weight gradients: classes by decreasing row count
 };
 
 __device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
@@ -54,15 +55,23 @@ __device__ __forceinline__ float sigmoid_fast(float u) {
 }
 
 // ---------------------------------------------------------------- m-tile table
+// map[0] = number of m-tiles, map[4 + 4i ..] = {first row, end row, slot} of m-tile i.
+// order[c] = the class with the c-th largest number of rows (ties: lower index first).
 __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict__ slot_offsets,
-                                                       int S, int32_t* __restrict__ map) {
+                                                       const int32_t* __restrict__ first_slot, int S,
+                                                       int E, int32_t* __restrict__ map,
+                                                       int32_t* __restrict__ order) {
   __shared__ int32_t part[256];
+  __shared__ int32_t rows[1024];
   const int tid = threadIdx.x;
   const int per = (S + 255) / 256;
   const int q0 = tid * per, q1 = min(S, q0 + per);
   int mine = 0;
   for (int q = q0; q < q1; ++q) mine += (slot_offsets[q + 1] - slot_offsets[q] + GEMM_BM - 1) / GEMM_BM;
   part[tid] = mine;
+  if (first_slot) {
+    for (int e = tid; e < E; e += 256) rows[e] = slot_offsets[first_slot[e + 1]] - slot_offsets[first_slot[e]];
+  }
   __syncthreads();
   for (int o = 1; o < 256; o <<= 1) {  // Hillis-Steele inclusive scan
     const int add = tid >= o ? part[tid - o] : 0;
@@ -79,6 +88,13 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
       map[4 + 4 * t + 1] = min(e, r + GEMM_BM);
       map[4 + 4 * t + 2] = q;
       map[4 + 4 * t + 3] = 0;
+    }
+  }
+  if (first_slot) {
+    for (int e = tid; e < E; e += 256) {
+      int rank = 0;
+      for (int j = 0; j < E; ++j) rank += (rows[j] > rows[e] || (rows[j] == rows[e] && j < e)) ? 1 : 0;
+      order[rank] = e;
     }
   }
 }
@@ -159,7 +175,9 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
     group = p.tile_map[4 + 4 * mt + 2];
     K = p.K;
   } else {
-    group = blockIdx.z;
+    // classes in order of decreasing row count: the long reductions start first and the
+    // short (or empty, store-only) tiles fill in behind them
+    group = p.class_order[blockIdx.z];
     row0 = blockIdx.y * BM;
     row1 = min(p.M, row0 + BM);
     kbeg = p.slot_offsets[p.first_slot[group]];
@@ -702,7 +720,7 @@ extern "C" int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_
   const WsLayout L = ws_layout(cfg);
   int32_t* map = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.tile_map);
   const int max_mtiles = (int)(A / GEMM_BM) + cfg->S_tot;
-  SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, cfg->S_tot, map)));
+  SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, nullptr, cfg->S_tot, cfg->E, map, nullptr)));
 
   GemmParams p = {};
   p.tile_map = map;
@@ -738,14 +756,16 @@ extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void*
   void* dUV = static_cast<char*>(ws) + L.duv;
   const int max_mtiles = (int)(A / GEMM_BM) + cfg->S_tot;
 
+  int32_t* order = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.class_order);
   GemmParams p = {};
   p.tile_map = map;
   p.slot_offsets = slot_offsets;
   p.first_slot = first_slot;
+  p.class_order = order;
   p.d = cfg->d;
   p.f = cfg->f;
+  SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, first_slot, cfg->S_tot, cfg->E, map, order)));
   if (A > 0) {
-    SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, cfg->S_tot, map)));
     // dh = dYp W2, then du, dv
     const bool bf16 = cfg->dtype == SYMI_BF16;
     void* dHbuf = static_cast<char*>(ws) + L.dh;
