@@ -68,6 +68,41 @@ def measured_traffic(workload, kernel):
         return None
 
 
+def survival(args):
+    """Token survival (Sec. 3.4, Sec. 5.2) per iteration of a config under capacity_factor,
+    for the placement that mimics the previous iteration and for the static uniform one.
+    Integer stages only (route, place, capacity-limited dispatch); one JSON line per iteration."""
+    import torch
+    import paper_2504_19925_amd as symi
+    import workloads as wl
+    from tests import harness as Hn
+
+    c = wl.get_config(args.config)
+    cfg = Hn.make_cfg(c)
+    dev = "cuda"
+    i32 = dict(dtype=torch.int32, device=dev)
+    ws = torch.empty(symi.symi_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+    X = torch.zeros(c.T, c.d, dtype=cfg.torch_dtype, device=dev)
+    Xp = torch.empty(c.A, c.d, dtype=cfg.torch_dtype, device=dev)
+    idx = torch.empty(c.T, c.k, **i32)
+    gate = torch.empty(c.T, c.k, dtype=torch.float32, device=dev)
+    hist = torch.empty(c.E, **i32)
+    counts, placement, first = torch.empty(c.E, **i32), torch.empty(c.S_tot, **i32), torch.empty(c.E + 1, **i32)
+    roa, aor, off = torch.empty(c.A, **i32), torch.empty(c.A, **i32), torch.empty(c.S_tot + 1, **i32)
+    cap = symi.symi_slot_capacity(cfg, args.survival)
+    prev = torch.zeros(c.E, **i32)
+    for it in range(max(c.iters, 1)):
+        logits = wl.make_logits(c, it).to(dev)
+        symi.symi_route(cfg, logits, idx, gate, hist)
+        out = {"workload": c.name, "iteration": it, "capacity_factor": args.survival, "slot_capacity": cap}
+        for mode, pop in (("adaptive", prev), ("uniform", torch.zeros(c.E, **i32))):
+            symi.symi_place(cfg, pop, counts, placement, first)
+            symi.symi_dispatch_capacity(cfg, cap, X, idx, hist, counts, first, roa, aor, off, Xp, ws)
+            out["survival_" + mode] = round(int(off[-1]) / c.A, 5)
+        print(json.dumps(out))
+        prev = hist.clone()
+
+
 def calibrate_copy():
     """A plain copy of known size, to scale the HBM counters: 8 copies of 1 GiB."""
     import torch
@@ -244,9 +279,15 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device copy (reference for the HBM traffic counters)")
+    ap.add_argument("--survival", type=float, default=None, metavar="CAPACITY_FACTOR",
+                    help="print the token survival per iteration of --config under this capacity "
+                         "factor (adaptive vs. uniform placement) instead of the benchmark")
     args = ap.parse_args()
     if args.calibrate_copy:
         calibrate_copy()
+        return
+    if args.survival is not None:
+        survival(args)
         return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share of the path; --gpus must be 1 "

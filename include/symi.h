@@ -4,7 +4,7 @@
  * One GPU's share of one adaptive-replication MoE training iteration
  * (Symi, arXiv 2504.19925, Sec. 3.2, Fig. 5 steps 1-8):
  *
- *   forward    symi_route -> symi_dispatch -> symi_expert_fwd -> symi_combine
+ *   forward    symi_route -> symi_dispatch (or symi_dispatch_capacity) -> symi_expert_fwd -> symi_combine
  *   backward   symi_combine_bwd -> symi_expert_bwd -> symi_dispatch_bwd -> symi_route_bwd
  *   optimizer  symi_place (next placement, Algorithm 1) -> symi_adam_to_replicas
  *
@@ -101,6 +101,28 @@ int symi_dispatch(const symi_cfg* cfg, const void* X, const int32_t* idx, const 
                   const int32_t* counts, const int32_t* first_slot, int32_t* row_of_assign,
                   int32_t* assign_of_row, int32_t* slot_offsets, void* Xp, void* ws,
                   void* stream);
+
+/* Expert capacity under adaptive replication (Sec. 3.4):
+ *   slot_capacity = capacity_factor * tokens_per_batch / (s*N),  capacity(e_i) = slot_capacity * r_i.
+ * HOST function: returns slot_capacity for cfg (tokens_per_batch = T*k assignments), the
+ * product evaluated in binary64 as capacity_factor * (T*k) / S_tot and rounded up to whole
+ * rows (at least 1); a negative error code if cfg or capacity_factor (<= 0) is invalid.  */
+int symi_slot_capacity(const symi_cfg* cfg, double capacity_factor);
+
+/* symi_dispatch with that capacity rule: of the hist[e] assignments of class e, the first
+ * slot_capacity * counts[e] in stable (assignment id) order are kept, the rest are dropped.
+ *   row_of_assign [A] out: row of a kept assignment, -1 for a dropped one;
+ *   assign_of_row [A] out: entries [0, A') valid, A' = number of kept assignments;
+ *   slot_offsets [S_tot+1] out over the kept rows (no slot exceeds slot_capacity rows),
+ *   slot_offsets[S_tot] = A': the token survival rate of the iteration (Sec. 5.2) is A'/A;
+ *   Xp [A,d] out: rows [0, A') written.
+ * symi_expert_fwd/bwd work on slot_offsets and so on the kept rows only; symi_combine,
+ * symi_combine_bwd and symi_dispatch_bwd skip dropped assignments (they contribute
+ * nothing to Y, dX, and get dgate = 0); gates are not renormalised after a drop.        */
+int symi_dispatch_capacity(const symi_cfg* cfg, int slot_capacity, const void* X, const int32_t* idx,
+                           const int32_t* hist, const int32_t* counts, const int32_t* first_slot,
+                           int32_t* row_of_assign, int32_t* assign_of_row, int32_t* slot_offsets,
+                           void* Xp, void* ws, void* stream);
 
 /* Backward of the gather: dX[t] = sum_j dXp[row_of_assign[t*k+j]] (j ascending). */
 int symi_dispatch_bwd(const symi_cfg* cfg, const void* dXp, const int32_t* row_of_assign,

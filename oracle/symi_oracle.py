@@ -12,6 +12,8 @@ What each function follows
   place_float_literal   the same listing evaluated in binary64 as printed (a second
                     implementation used as a pin; not normative)
   dispatch          Sec. 3.2 step 2 (tokens of a class are spread over its replicas)
+  slot_capacity, dispatch_capacity   Sec. 3.4: capacity(e_i) = slot_capacity * r_i; the
+                    assignments of a class beyond its capacity are dropped
   moe_forward       Sec. 2.1: Y[t] = sum_j gate[t,j] * FFN_{idx[t,j]}(X[t]), SwiGLU FFN
   moe_backward      the derivative of that definition (Sec. 3.2 step 3 only changes
                     where the class gradient is summed, not its value)
@@ -24,7 +26,10 @@ Readings where the paper is silent (each is stated at its function):
   near-equal blocks in stable order; the gradient of a class is the plain sum over
   its rows times a caller-supplied scale; Adam has bias correction, eps outside the
   square root and decoupled weight decay; a shard is a contiguous range of the flat
-  vector [W1 | W2] of a class.  These conventions have no external pin ("parity
+  vector [W1 | W2] of a class; slot_capacity is rounded up to whole rows, the kept
+  assignments of a class are its first ones in assignment order, a dropped assignment
+  contributes nothing and the remaining gates are not renormalised.  These conventions
+  have no external pin ("parity
   unpinned" beyond self-consistency); everything else is pinned in tests/ by brute
   force, invariants, closed forms, finite differences or library routines.
 """
@@ -164,6 +169,46 @@ def dispatch(idx, counts, first_slot):
             slot_offsets[int(first_slot[e]) + i] = O[e] + (i * int(c[e])) // r
     slot_offsets[S_tot] = A
     return row_of_assign, assign_of_row, slot_offsets
+
+
+def slot_capacity(capacity_factor, A, S_tot):
+    """Sec. 3.4: slot_capacity = capacity_factor * tokens_per_batch / (s*N) with
+    tokens_per_batch = A assignments and s*N = S_tot slots, evaluated in binary64 in that
+    order and rounded up to whole rows (at least one)."""
+    x = np.float64(capacity_factor) * np.float64(A) / np.float64(S_tot)
+    return max(1, int(np.ceil(x)))
+
+
+def dispatch_capacity(idx, counts, first_slot, slot_cap):
+    """dispatch under the capacity rule of Sec. 3.4: class e keeps at most
+    slot_cap * counts[e] assignments, the first ones in assignment order.
+
+    Returns row_of_assign [A] (-1 = dropped), assign_of_row [A'] (kept rows only),
+    slot_offsets [S_tot+1] over the kept rows, keep [A] bool.  The survival rate of the
+    iteration (Sec. 5.2) is A'/A.
+    """
+    cls = np.asarray(idx).ravel().astype(np.int64)
+    A = cls.size
+    E = len(counts)
+    order = np.argsort(cls, kind="stable")           # assignments in stable class order
+    c = np.bincount(cls, minlength=E)
+    O = np.concatenate([[0], np.cumsum(c)])
+    rank = np.empty(A, dtype=np.int64)                # position of an assignment inside its class
+    rank[order] = np.arange(A) - O[cls[order]]
+    cap = np.minimum(np.asarray(counts, dtype=np.int64) * int(slot_cap), A)
+    keep = rank < cap[cls]
+    ck = np.minimum(c, cap)                           # kept rows per class
+    Ok = np.concatenate([[0], np.cumsum(ck)])
+    row_of_assign = np.where(keep, Ok[cls] + rank, -1).astype(np.int32)
+    assign_of_row = order[keep[order]].astype(np.int32)
+    S_tot = int(first_slot[E])
+    slot_offsets = np.zeros(S_tot + 1, dtype=np.int32)
+    for e in range(E):
+        r = int(counts[e])
+        for i in range(r):
+            slot_offsets[int(first_slot[e]) + i] = Ok[e] + (i * int(ck[e])) // r
+    slot_offsets[S_tot] = Ok[E]
+    return row_of_assign, assign_of_row, slot_offsets, keep
 
 
 # ------------------------------------------------------------------------- forward

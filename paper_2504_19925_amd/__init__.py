@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     symi_place,
     symi_place_host,
     symi_dispatch,
+    symi_slot_capacity,
+    symi_dispatch_capacity,
     symi_dispatch_bwd,
     symi_expert_fwd,
     symi_expert_bwd,

@@ -15,7 +15,8 @@ _LIB = None
 
 EXPORTS = [
     "symi_validate", "symi_workspace_bytes", "symi_last_error", "symi_route", "symi_route_bwd",
-    "symi_place", "symi_place_host", "symi_dispatch", "symi_dispatch_bwd", "symi_expert_fwd",
+    "symi_place", "symi_place_host", "symi_dispatch", "symi_slot_capacity",
+    "symi_dispatch_capacity", "symi_dispatch_bwd", "symi_expert_fwd",
     "symi_expert_bwd", "symi_combine", "symi_combine_bwd", "symi_adam_to_replicas",
     "symi_timing_enable", "symi_timing_reset", "symi_timing_read", "symi_kernel_count",
     "symi_kernel_name",
@@ -70,6 +71,8 @@ def lib():
             "symi_place": [cfgp, ip, ip, ip, ip, vp],
             "symi_place_host": [cfgp, ip, ip, ip, ip],
             "symi_dispatch": [cfgp, vp, ip, ip, ip, ip, ip, ip, ip, vp, vp, vp],
+            "symi_slot_capacity": [cfgp, ctypes.c_double],
+            "symi_dispatch_capacity": [cfgp, ctypes.c_int, vp, ip, ip, ip, ip, ip, ip, ip, vp, vp, vp],
             "symi_dispatch_bwd": [cfgp, vp, ip, vp, vp],
             "symi_expert_fwd": [cfgp, vp, ip, vp, vp, vp, vp, vp, vp, vp],
             "symi_expert_bwd": [cfgp, vp, vp, vp, vp, ip, ip, vp, vp, vp, fp, fp, vp, vp],
@@ -203,6 +206,26 @@ def symi_dispatch(cfg, X, idx, hist, counts, first_slot, row_of_assign, assign_o
         _dev(assign_of_row, I32, "assign_of_row", cfg.A),
         _dev(slot_offsets, I32, "slot_offsets", cfg.S_tot + 1), _dev(Xp, dt, "Xp", cfg.A * cfg.d),
         _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), "symi_dispatch")
+
+
+def symi_slot_capacity(cfg, capacity_factor):
+    rc = lib().symi_slot_capacity(ctypes.byref(cfg), float(capacity_factor))
+    if rc < 0:
+        _check(rc, "symi_slot_capacity")
+    return rc
+
+
+def symi_dispatch_capacity(cfg, slot_capacity, X, idx, hist, counts, first_slot, row_of_assign,
+                           assign_of_row, slot_offsets, Xp, ws):
+    dt = cfg.torch_dtype
+    _check(lib().symi_dispatch_capacity(
+        ctypes.byref(cfg), int(slot_capacity), _dev(X, dt, "X", cfg.T * cfg.d),
+        _dev(idx, I32, "idx", cfg.A), _dev(hist, I32, "hist", cfg.E),
+        _dev(counts, I32, "counts", cfg.E), _dev(first_slot, I32, "first_slot", cfg.E + 1),
+        _dev(row_of_assign, I32, "row_of_assign", cfg.A),
+        _dev(assign_of_row, I32, "assign_of_row", cfg.A),
+        _dev(slot_offsets, I32, "slot_offsets", cfg.S_tot + 1), _dev(Xp, dt, "Xp", cfg.A * cfg.d),
+        _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), "symi_dispatch_capacity")
 
 
 def symi_dispatch_bwd(cfg, dXp, row_of_assign, dX):

@@ -56,6 +56,8 @@ WsLayout ws_layout(const symi_cfg* c) {
   size_t off = 0;
   L.blk_counts = off;
   off += align_up((nblk + 1) * c->E * sizeof(int32_t), 256);
+  L.class_tab = off;
+  off += align_up((size_t)3 * c->E * sizeof(int32_t), 256);
   L.tile_map = off;
   off += align_up((4 + 4 * mtiles) * sizeof(int32_t), 256);
   L.class_order = off;

@@ -72,6 +72,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // Workspace layout (byte offsets inside the caller's `ws`), one place for all users.
 struct WsLayout {
   size_t blk_counts;   // dispatch: [nblk][E] i32 per-block class counts, then bases
+  size_t class_tab;    // capacity-limited dispatch: per class {offset, kept offset, capacity}
   size_t tile_map;     // expert fwd/bwd: m-tile table, see gemm.hip
   size_t class_order;  // expert bwd: classes by decreasing row count
   size_t duv;          // expert bwd: dUV [A,2f] in the activation dtype

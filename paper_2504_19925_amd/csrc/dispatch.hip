@@ -13,6 +13,13 @@
 //      classes is a popcount over a match mask built from ballots, across wavefronts
 //      and passes it is a small LDS prefix.
 // Row moves are 16-byte vector loads/stores, one row spread over consecutive lanes.
+//
+// symi_dispatch_capacity is the same permutation under the capacity rule of Sec. 3.4:
+// class e may occupy slot_capacity * r_e rows (r_e = its replicas in the current
+// placement); its assignments beyond that, in stable order, are dropped (row -1), the
+// kept ones are packed without gaps and spread over the replicas as before.
+#include <math.h>
+
 #include "common.h"
 
 namespace symi {
@@ -36,26 +43,41 @@ __global__ __launch_bounds__(DT) void chunk_count_kernel(const int32_t* __restri
 }
 
 // grid = E workgroups; workgroup e scans column e of blk_counts in place into bases.
+// slot_cap > 0 switches the capacity rule on: class i keeps min(hist[i], slot_cap * counts[i])
+// rows; slot_offsets then describes the kept rows only and tab[3e..] = {O_e, offset of the
+// class among the kept rows, capacity of the class} tells the ranking kernel what to drop.
 __global__ __launch_bounds__(DT) void chunk_scan_kernel(int32_t* __restrict__ blk_counts, int nblk,
                                                         int E, int S, int A,
                                                         const int32_t* __restrict__ hist,
                                                         const int32_t* __restrict__ counts,
                                                         const int32_t* __restrict__ first_slot,
-                                                        int32_t* __restrict__ slot_offsets) {
+                                                        int32_t* __restrict__ slot_offsets,
+                                                        int slot_cap, int32_t* __restrict__ tab) {
   __shared__ int32_t wsum[DT / 64];
   __shared__ int32_t carry_s;
-  __shared__ int32_t red[DT / 64];
+  __shared__ int32_t red[2][DT / 64];
   const int e = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  auto cap_of = [&](int i) -> int {
+    if (slot_cap <= 0) return A;
+    const long long c = (long long)slot_cap * counts[i];
+    return c < A ? (int)c : A;
+  };
 
-  // class offset O_e = rows of all lower classes
-  int part = 0;
-  for (int i = threadIdx.x; i < e; i += DT) part += hist[i];
-  for (int m = 32; m >= 1; m >>= 1) part += __shfl_xor(part, m, 64);
-  if (lane == 0) red[wave] = part;
+  // class offset O_e = rows of all lower classes (all of them / the kept ones)
+  int part = 0, partk = 0;
+  for (int i = threadIdx.x; i < e; i += DT) {
+    part += hist[i];
+    partk += min(hist[i], cap_of(i));
+  }
+  for (int m = 32; m >= 1; m >>= 1) {
+    part += __shfl_xor(part, m, 64);
+    partk += __shfl_xor(partk, m, 64);
+  }
+  if (lane == 0) { red[0][wave] = part; red[1][wave] = partk; }
   __syncthreads();
-  int O_e = 0;
-  for (int w = 0; w < DT / 64; ++w) O_e += red[w];
+  int O_e = 0, Ok_e = 0;
+  for (int w = 0; w < DT / 64; ++w) { O_e += red[0][w]; Ok_e += red[1][w]; }
   if (threadIdx.x == 0) carry_s = O_e;
   __syncthreads();
 
@@ -78,16 +100,24 @@ __global__ __launch_bounds__(DT) void chunk_scan_kernel(int32_t* __restrict__ bl
   }
 
   // replica i of class e owns rows O_e + floor(i*c_e/r_e) .. O_e + floor((i+1)*c_e/r_e)
-  const int r = counts[e], c_e = hist[e], F = first_slot[e];
+  // (c_e and O_e counted over the kept rows)
+  const int r = counts[e], F = first_slot[e];
+  const int c_e = min(hist[e], cap_of(e));
   for (int i = threadIdx.x; i < r; i += DT)
-    slot_offsets[F + i] = O_e + (int)(((long long)i * c_e) / r);
-  if (e == E - 1 && threadIdx.x == 0) slot_offsets[S] = A;
+    slot_offsets[F + i] = Ok_e + (int)(((long long)i * c_e) / r);
+  if (e == E - 1 && threadIdx.x == 0) slot_offsets[S] = Ok_e + c_e;
+  if (tab && threadIdx.x == 0) {
+    tab[3 * e] = O_e;
+    tab[3 * e + 1] = Ok_e;
+    tab[3 * e + 2] = cap_of(e);
+  }
 }
 
 __global__ __launch_bounds__(DT) void chunk_rank_kernel(const int32_t* __restrict__ cls, int A, int E,
                                                         const int32_t* __restrict__ bases,
                                                         int32_t* __restrict__ row_of_assign,
-                                                        int32_t* __restrict__ assign_of_row) {
+                                                        int32_t* __restrict__ assign_of_row,
+                                                        const int32_t* __restrict__ tab) {
   extern __shared__ int32_t sm[];
   int32_t* running = sm;           // [E] rows of class e already placed by this workgroup (+ base)
   int32_t* wcnt = sm + E;          // [4][E] per-wavefront counts of the current pass
@@ -118,8 +148,13 @@ __global__ __launch_bounds__(DT) void chunk_rank_kernel(const int32_t* __restric
     if (valid) {
       int row = running[c] + rank_in_wave;
       for (int w = 0; w < wave; ++w) row += wcnt[w * E + c];
+      if (tab) {
+        // capacity rule: the first cap_e assignments of the class (stable order) are kept
+        const int rho = row - tab[3 * c];
+        row = rho < tab[3 * c + 2] ? tab[3 * c + 1] + rho : -1;
+      }
       row_of_assign[a] = row;
-      if ((unsigned)row < (unsigned)A) assign_of_row[row] = a;   // false only if hist disagrees with idx
+      if ((unsigned)row < (unsigned)A) assign_of_row[row] = a;   // false if dropped (or hist disagrees with idx)
     }
     __syncthreads();
     for (int i = threadIdx.x; i < E; i += DT) {
@@ -136,7 +171,9 @@ __global__ __launch_bounds__(DT) void chunk_rank_kernel(const int32_t* __restric
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ src,
                                                           uint4* __restrict__ dst,
                                                           const int32_t* __restrict__ map, int div,
-                                                          long long n_vec, int vec_per_row) {
+                                                          long long n_vec, int vec_per_row,
+                                                          const int32_t* __restrict__ n_rows) {
+  if (n_rows) n_vec = (long long)*n_rows * vec_per_row;   // only the kept rows exist
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n_vec;
        i += (long long)gridDim.x * 256) {
     const long long row = i / vec_per_row;
@@ -194,6 +231,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ s
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int j = 0; j < k; ++j) {
       const long long row = roa[t * k + j];
+      if (row < 0) continue;   // dropped by the capacity rule: contributes nothing
       const float g = w ? w[t * k + j] : 1.f;
       float x[8];
       load_piece<BF16>(src, row * pieces_per_row + c, x);
@@ -219,6 +257,10 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const void* __restrict
   for (long long t = wave0; t < T; t += (long long)gridDim.x * 4) {
     for (int j = 0; j < k; ++j) {
       const long long row = roa[t * k + j];
+      if (row < 0) {   // dropped by the capacity rule: the output does not depend on this gate
+        if (lane == 0) dgate[t * k + j] = 0.f;
+        continue;
+      }
       const float g = gate[t * k + j];
       float dot = 0.f;
       for (int c = lane; c < pieces_per_row; c += 64) {
@@ -249,34 +291,67 @@ static int grid_for(long long work_items, int per_block) {
 
 using namespace symi;
 
-extern "C" int symi_dispatch(const symi_cfg* cfg, const void* X, const int32_t* idx,
-                             const int32_t* hist, const int32_t* counts, const int32_t* first_slot,
-                             int32_t* row_of_assign, int32_t* assign_of_row, int32_t* slot_offsets,
-                             void* Xp, void* ws, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_dispatch")) return rc;
-  SYMI_REQUIRE(hist && counts && first_slot && slot_offsets && ws, "symi_dispatch", "NULL pointer");
-  SYMI_REQUIRE(cfg->T == 0 || (X && idx && row_of_assign && assign_of_row && Xp), "symi_dispatch",
-               "NULL pointer");
+static int dispatch_impl(const char* who, const symi_cfg* cfg, int slot_cap, const void* X,
+                         const int32_t* idx, const int32_t* hist, const int32_t* counts,
+                         const int32_t* first_slot, int32_t* row_of_assign, int32_t* assign_of_row,
+                         int32_t* slot_offsets, void* Xp, void* ws, void* stream) {
+  if (int rc = check_cfg(cfg, who)) return rc;
+  SYMI_REQUIRE(hist && counts && first_slot && slot_offsets && ws, who, "NULL pointer");
+  SYMI_REQUIRE(cfg->T == 0 || (X && idx && row_of_assign && assign_of_row && Xp), who, "NULL pointer");
   hipStream_t st = as_stream(stream);
   const int E = cfg->E, A = cfg->T * cfg->k;
   const WsLayout L = ws_layout(cfg);
   int32_t* blk = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.blk_counts);
+  int32_t* tab = slot_cap > 0 ? reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.class_tab) : nullptr;
   const int nblk = cdiv(A, DISPATCH_CHUNK);
   if (nblk > 0)
     SYMI_TIMED(K_CHUNK_COUNT, st, (chunk_count_kernel<<<nblk, DT, E * sizeof(int32_t), st>>>(idx, A, E, blk)));
   SYMI_TIMED(K_CHUNK_SCAN, st, (chunk_scan_kernel<<<E, DT, 0, st>>>(blk, nblk, E, cfg->S_tot, A, hist, counts,
-                                                                    first_slot, slot_offsets)));
+                                                                    first_slot, slot_offsets, slot_cap, tab)));
   if (nblk > 0) {
     SYMI_TIMED(K_CHUNK_RANK, st, (chunk_rank_kernel<<<nblk, DT, (size_t)(1 + DT / 64) * E * sizeof(int32_t), st>>>(
-        idx, A, E, blk, row_of_assign, assign_of_row)));
+        idx, A, E, blk, row_of_assign, assign_of_row, tab)));
     const int w = cfg->dtype == SYMI_BF16 ? 2 : 4;
     const int vpr = cfg->d * w / 16;
     const long long nvec = (long long)A * vpr;
     SYMI_TIMED(K_GATHER, st, (gather_rows_kernel<<<grid_for(nvec, 256 * 4), 256, 0, st>>>(
-        static_cast<const uint4*>(X), static_cast<uint4*>(Xp), assign_of_row, cfg->k, nvec, vpr)));
+        static_cast<const uint4*>(X), static_cast<uint4*>(Xp), assign_of_row, cfg->k, nvec, vpr,
+        slot_cap > 0 ? slot_offsets + cfg->S_tot : nullptr)));
   }
-  SYMI_LAUNCH_CHECK("symi_dispatch");
+  SYMI_LAUNCH_CHECK(who);
   return SYMI_OK;
+}
+
+extern "C" int symi_dispatch(const symi_cfg* cfg, const void* X, const int32_t* idx,
+                             const int32_t* hist, const int32_t* counts, const int32_t* first_slot,
+                             int32_t* row_of_assign, int32_t* assign_of_row, int32_t* slot_offsets,
+                             void* Xp, void* ws, void* stream) {
+  return dispatch_impl("symi_dispatch", cfg, 0, X, idx, hist, counts, first_slot, row_of_assign,
+                       assign_of_row, slot_offsets, Xp, ws, stream);
+}
+
+extern "C" int symi_slot_capacity(const symi_cfg* cfg, double capacity_factor) {
+  if (int rc = check_cfg(cfg, "symi_slot_capacity")) return rc;
+  SYMI_REQUIRE(capacity_factor > 0.0 && capacity_factor <= 1e6, "symi_slot_capacity",
+               "capacity_factor must lie in (0, 1e6]");
+  // slot_capacity = capacity_factor * tokens_per_batch / (s N), evaluated in binary64 in this
+  // order and rounded up to whole rows
+  const double x = capacity_factor * (double)((long long)cfg->T * cfg->k) / (double)cfg->S_tot;
+  const double c = ceil(x);
+  if (c < 1.0) return 1;
+  if (c > 2147483647.0) return 2147483647;
+  return (int)c;
+}
+
+extern "C" int symi_dispatch_capacity(const symi_cfg* cfg, int slot_capacity, const void* X,
+                                      const int32_t* idx, const int32_t* hist, const int32_t* counts,
+                                      const int32_t* first_slot, int32_t* row_of_assign,
+                                      int32_t* assign_of_row, int32_t* slot_offsets, void* Xp,
+                                      void* ws, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_dispatch_capacity")) return rc;
+  SYMI_REQUIRE(slot_capacity >= 1, "symi_dispatch_capacity", "slot_capacity must be >= 1");
+  return dispatch_impl("symi_dispatch_capacity", cfg, slot_capacity, X, idx, hist, counts, first_slot,
+                       row_of_assign, assign_of_row, slot_offsets, Xp, ws, stream);
 }
 
 extern "C" int symi_dispatch_bwd(const symi_cfg* cfg, const void* dXp, const int32_t* row_of_assign,

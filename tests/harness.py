@@ -80,11 +80,16 @@ class State:
         torch.index_select(self.W1c, 0, pl, out=self.W1s)
         torch.index_select(self.W2c, 0, pl, out=self.W2s)
 
-    def forward(self, X, logits):
+    def forward(self, X, logits, slot_cap=None):
+        """slot_cap: rows a slot may take (capacity-limited dispatch); None = dropless."""
         s, cfg = self, self.cfg
         symi.symi_route(cfg, logits, s.idx, s.gate, s.hist)
-        symi.symi_dispatch(cfg, X, s.idx, s.hist, s.counts, s.first_slot, s.row_of_assign,
-                           s.assign_of_row, s.slot_offsets, s.Xp, s.ws)
+        if slot_cap is None:
+            symi.symi_dispatch(cfg, X, s.idx, s.hist, s.counts, s.first_slot, s.row_of_assign,
+                               s.assign_of_row, s.slot_offsets, s.Xp, s.ws)
+        else:
+            symi.symi_dispatch_capacity(cfg, slot_cap, X, s.idx, s.hist, s.counts, s.first_slot,
+                                        s.row_of_assign, s.assign_of_row, s.slot_offsets, s.Xp, s.ws)
         symi.symi_expert_fwd(cfg, s.Xp, s.slot_offsets, s.W1s, s.W2s, s.UV, s.H, s.Yp, s.ws)
         symi.symi_combine(cfg, s.Yp, s.row_of_assign, s.gate, s.Y)
 

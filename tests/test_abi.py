@@ -70,3 +70,21 @@ def test_binding_refuses_cpu_tensors_for_device_calls():
     with pytest.raises(symi.SymiError):
         symi.symi_route(cfg, z, torch.zeros(64, 2, dtype=torch.int32), torch.zeros(64, 2),
                         torch.zeros(8, dtype=torch.int32))
+
+
+def test_slot_capacity_host_function_matches_oracle():
+    """symi_slot_capacity is a host computation: Sec. 3.4's slot_capacity, rounded up."""
+    rng = random.Random(5)
+    for _ in range(500):
+        E = rng.randint(1, 64)
+        S = rng.randint(E, 4 * E)
+        k = rng.randint(1, min(E, 8))
+        T = rng.randint(0, 5000)
+        cfg = symi.SymiCfg.make(T=T, E=E, k=k, d=64, f=64, S_tot=S, N=1, shard=0, dtype="f32")
+        cf = rng.choice([0.25, 0.5, 1.0, 1.25, 1.5, 2.0, 4.0, rng.uniform(0.01, 8.0)])
+        assert symi.symi_slot_capacity(cfg, cf) == O.slot_capacity(cf, T * k, S)
+    cfg = symi.SymiCfg.make(T=8192, E=64, k=2, d=1024, f=4096, S_tot=96, N=8, shard=0, dtype="bf16")
+    assert symi.symi_slot_capacity(cfg, 1.0) == 171 and symi.symi_slot_capacity(cfg, 1.5) == 256
+    for bad in (0.0, -1.0, float("nan")):
+        with pytest.raises(symi.SymiError):
+            symi.symi_slot_capacity(cfg, bad)
