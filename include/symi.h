@@ -171,6 +171,47 @@ int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp, const float*
                           const int32_t* first_slot_next, void* W1_slots, void* W2_slots,
                           void* stream);
 
+/* ---- host helpers for the multi-rank part of the method (no GPU work; all pointers HOST).
+ * Slot q of a placement lives on rank q / s, s = S_tot / N (S_tot must divide by N). */
+
+/* Gradient collection, Algorithm 2 (App. A.4; Sec. 4.3): the one rank that sends the
+ * gradient shard of class exp_id to the optimizer partition on `rank`: `rank` itself if
+ * it hosts the class, else host number (rank mod #hosts) of the ascending list of ranks
+ * hosting it.  Returns the source rank (>= 0) or a negative error code.              */
+int symi_grad_source(const symi_cfg* cfg, const int32_t* placement, int exp_id, int rank);
+
+/* The communication tuples of `rank` for one iteration (Algorithm 2, collect_grads):
+ *   recv_src [E] out: rank r receives the shard of class e for its partition from recv_src[e];
+ *   send_offsets [E+1], send_dst [send_capacity] out: for a class e hosted on `rank`, the
+ *   destinations send_dst[send_offsets[e] .. send_offsets[e+1]) whose partition this rank
+ *   serves (ascending; empty for classes not hosted here).
+ * Returns the number of send tuples, or a negative error code (SYMI_EINVAL also when
+ * send_capacity is too small; N entries per hosted class always suffice).            */
+int symi_collect_grads(const symi_cfg* cfg, const int32_t* placement, int rank, int32_t* recv_src,
+                       int32_t* send_offsets, int32_t* send_dst, int send_capacity);
+
+/* Communication group management (Sec. 4.2): index in [0, N(N-1)/2) of the pre-registered
+ * group made of the consecutive ranks first_rank .. last_rank (first_rank < last_rank),
+ * groups ordered by first rank, then by last rank.                                    */
+int symi_rank_group(int N, int first_rank, int last_rank);
+
+/* The cost model of Sec. 3.3 (App. A.1; App. A.5 with bw_pci = INFINITY).  Sizes in bytes
+ * (or any one unit), bandwidths in that unit per second.                              */
+typedef struct {
+  int E, N, s;            /* expert classes, ranks, slots per rank                        */
+  double G, W, O;         /* gradient, weight and optimizer-state size of ONE expert      */
+  double bw_pci, bw_net;  /* host link and network bandwidth per rank                     */
+} symi_cost_in;
+typedef struct {
+  double mem_static, mem_symi;                  /* (I)  optimizer memory, whole cluster   */
+  double data_grad_static, data_weight_static;  /* (II) data moved per iteration          */
+  double data_grad_symi, data_weight_symi;
+  double t_grad_static, t_weight_static;        /* (III) time of the two phases per rank  */
+  double t_grad_symi, t_weight_symi;
+  double extra_fraction;                        /* (T_symi - T_static) / T_static, G = W  */
+} symi_cost_out;
+int symi_comm_cost(const symi_cost_in* in, symi_cost_out* out);
+
 /* Measurement aid (not part of the method): while enabled, every kernel the library
  * launches is bracketed by two HIP events recorded on the launch stream, so that a
  * benchmark can read per-kernel durations of its own timed region.  Enabling it makes

@@ -17,6 +17,9 @@ What each function follows
   moe_forward       Sec. 2.1: Y[t] = sum_j gate[t,j] * FFN_{idx[t,j]}(X[t]), SwiGLU FFN
   moe_backward      the derivative of that definition (Sec. 3.2 step 3 only changes
                     where the class gradient is summed, not its value)
+  get_source, collect_grads     App. A.4, Algorithm 2 (gradient collection plan), Sec. 4.3
+  rank_group        Sec. 4.2 (groups of consecutive ranks)
+  comm_cost         Sec. 3.3 (I)-(III), App. A.5: memory, data volume, communication time
   adam_step, adam_to_replicas   Sec. 3.2 steps 4-8: Adam on the static 1/N shard of
                     every class, then the weight write into next iteration's slots
 
@@ -371,3 +374,69 @@ def adam_to_replicas(dW1, dW2, master_w, m, v, placement_next, N, n, hp, bf16,
         if a < b:
             flat2[q, a - n1:b - n1] = fresh[e, a - lo:b - lo]
     return w2, m2, v2
+
+
+# ------------------------------------------------------- multi-rank planning (host side)
+def hosts_of(placement, N, exp_id):
+    """Ranks hosting class exp_id, ascending; slot q lives on rank q // s, s = S_tot / N."""
+    s = len(placement) // N
+    return sorted({q // s for q in range(len(placement)) if int(placement[q]) == exp_id})
+
+
+def get_source(placement, N, exp_id, rank):
+    """Algorithm 2: the single rank that supplies class exp_id's gradient shard to the
+    optimizer partition on `rank`: that rank itself when it hosts the class, otherwise the
+    hosts take the destinations in turn (host number rank mod #hosts)."""
+    hosts = hosts_of(placement, N, exp_id)
+    if rank in hosts:
+        return rank
+    return hosts[rank % len(hosts)]
+
+
+def collect_grads(placement, N, E, rank):
+    """Algorithm 2: communication tuples of `rank`.  recv[e] = (source, rank) for every class;
+    send[e] = [(dst, dst), ...] for every class hosted on `rank`."""
+    recv = {e: (get_source(placement, N, e, rank), rank) for e in range(E)}
+    send = {}
+    for e in range(E):
+        if rank not in hosts_of(placement, N, e):
+            continue
+        send[e] = [(dst, dst) for dst in range(N) if get_source(placement, N, e, dst) == rank]
+    return recv, send
+
+
+def rank_group(N, first_rank, last_rank):
+    """Sec. 4.2: position of the group {first_rank..last_rank} among all groups of two or more
+    consecutive ranks, listed by first rank and then by last rank (N(N-1)/2 of them)."""
+    groups = [(a, b) for a in range(N) for b in range(a + 1, N)]
+    return groups.index((first_rank, last_rank))
+
+
+def comm_cost(E, N, s, G, W, O, bw_pci, bw_net, placement_counts=None):
+    """Sec. 3.3.  (I) memory E*(1/r)*r*O vs E*(1/N)*N*O; (II) data moved, for Symi summed
+    over the actual replica counts r_i (default: any counts summing to s*N); (III) per-rank
+    time of the gradient and the weight phase; extra = (T_symi - T_static) / T_static."""
+    from fractions import Fraction as Fr
+    E_, N_, s_ = Fr(E), Fr(N), Fr(s)
+    G_, W_, O_ = Fr(G), Fr(W), Fr(O)
+    r = s_ * N_ / E_                                  # static replication degree, eq. (1)
+    counts = [Fr(int(c)) for c in placement_counts] if placement_counts is not None else [r] * int(E)
+    assert sum(counts) == s_ * N_                     # eq. (2)
+    inf = bw_pci == float("inf")
+    pci = None if inf else Fr(bw_pci)
+    net = Fr(bw_net)
+    out = {
+        "mem_static": E_ * (1 / r) * r * O_,
+        "mem_symi": E_ * (1 / N_) * N_ * O_,
+        "data_grad_static": E_ * r * (G_ / r) * r,
+        "data_weight_static": E_ * r * (W_ / r) * r,
+        "data_grad_symi": sum(ri * (G_ / N_) * N_ for ri in counts),
+        "data_weight_symi": sum(N_ * (W_ / N_) * ri for ri in counts),
+    }
+    for nm, X in (("grad", G_), ("weight", W_)):
+        host = 0 if inf else E_ / N_ * X / pci
+        out[f"t_{nm}_static"] = host + (s_ * N_ - E_) / N_ * X / net
+        out[f"t_{nm}_symi"] = host + (s_ * N_ - s_) / N_ * X / net
+    ts = out["t_grad_static"] + out["t_weight_static"]
+    out["extra_fraction"] = (out["t_grad_symi"] + out["t_weight_symi"] - ts) / ts
+    return {k: float(v) for k, v in out.items()}

@@ -18,6 +18,10 @@ from .binding import (  # noqa: F401
     symi_place_host,
     symi_dispatch,
     symi_slot_capacity,
+    symi_grad_source,
+    symi_collect_grads,
+    symi_rank_group,
+    symi_comm_cost,
     symi_dispatch_capacity,
     symi_dispatch_bwd,
     symi_expert_fwd,

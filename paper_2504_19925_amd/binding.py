@@ -19,7 +19,7 @@ EXPORTS = [
     "symi_dispatch_capacity", "symi_dispatch_bwd", "symi_expert_fwd",
     "symi_expert_bwd", "symi_combine", "symi_combine_bwd", "symi_adam_to_replicas",
     "symi_timing_enable", "symi_timing_reset", "symi_timing_read", "symi_kernel_count",
-    "symi_kernel_name",
+    "symi_kernel_name", "symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost",
 ]
 
 
@@ -42,6 +42,19 @@ class SymiCfg(ctypes.Structure):
     @property
     def torch_dtype(self):
         return torch.bfloat16 if self.dtype == 1 else torch.float32
+
+
+class SymiCostIn(ctypes.Structure):
+    _fields_ = [("E", ctypes.c_int), ("N", ctypes.c_int), ("s", ctypes.c_int), ("G", ctypes.c_double),
+                ("W", ctypes.c_double), ("O", ctypes.c_double), ("bw_pci", ctypes.c_double),
+                ("bw_net", ctypes.c_double)]
+
+
+class SymiCostOut(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in (
+        "mem_static", "mem_symi", "data_grad_static", "data_weight_static", "data_grad_symi",
+        "data_weight_symi", "t_grad_static", "t_weight_static", "t_grad_symi", "t_weight_symi",
+        "extra_fraction")]
 
 
 class SymiAdam(ctypes.Structure):
@@ -84,6 +97,13 @@ def lib():
             fn = getattr(L, name)
             fn.argtypes = args
             fn.restype = ctypes.c_int
+        L.symi_grad_source.argtypes = [cfgp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int]
+        L.symi_collect_grads.argtypes = [cfgp, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        L.symi_rank_group.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        L.symi_comm_cost.argtypes = [ctypes.POINTER(SymiCostIn), ctypes.POINTER(SymiCostOut)]
+        for name in ("symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost"):
+            getattr(L, name).restype = ctypes.c_int
         L.symi_workspace_bytes.argtypes = [cfgp]
         L.symi_workspace_bytes.restype = ctypes.c_size_t
         L.symi_last_error.argtypes = []
@@ -226,6 +246,44 @@ def symi_dispatch_capacity(cfg, slot_capacity, X, idx, hist, counts, first_slot,
         _dev(assign_of_row, I32, "assign_of_row", cfg.A),
         _dev(slot_offsets, I32, "slot_offsets", cfg.S_tot + 1), _dev(Xp, dt, "Xp", cfg.A * cfg.d),
         _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), "symi_dispatch_capacity")
+
+
+def _host_i32(t, name, numel):
+    if not isinstance(t, torch.Tensor) or t.is_cuda or t.dtype != I32 or not t.is_contiguous() or t.numel() < numel:
+        raise SymiError(f"{name}: expected a contiguous CPU int32 tensor with >= {numel} elements")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def symi_grad_source(cfg, placement, exp_id, rank):
+    rc = lib().symi_grad_source(ctypes.byref(cfg), _host_i32(placement, "placement", cfg.S_tot),
+                                int(exp_id), int(rank))
+    if rc < 0:
+        _check(rc, "symi_grad_source")
+    return rc
+
+
+def symi_collect_grads(cfg, placement, rank, recv_src, send_offsets, send_dst):
+    rc = lib().symi_collect_grads(ctypes.byref(cfg), _host_i32(placement, "placement", cfg.S_tot), int(rank),
+                                  _host_i32(recv_src, "recv_src", cfg.E),
+                                  _host_i32(send_offsets, "send_offsets", cfg.E + 1),
+                                  _host_i32(send_dst, "send_dst", 0), int(send_dst.numel()))
+    if rc < 0:
+        _check(rc, "symi_collect_grads")
+    return rc
+
+
+def symi_rank_group(N, first_rank, last_rank):
+    rc = lib().symi_rank_group(int(N), int(first_rank), int(last_rank))
+    if rc < 0:
+        _check(rc, "symi_rank_group")
+    return rc
+
+
+def symi_comm_cost(E, N, s, G, W, O, bw_pci, bw_net):
+    cin = SymiCostIn(int(E), int(N), int(s), float(G), float(W), float(O), float(bw_pci), float(bw_net))
+    out = SymiCostOut()
+    _check(lib().symi_comm_cost(ctypes.byref(cin), ctypes.byref(out)), "symi_comm_cost")
+    return {n: getattr(out, n) for n, _ in SymiCostOut._fields_}
 
 
 def symi_dispatch_bwd(cfg, dXp, row_of_assign, dX):

@@ -1,0 +1,138 @@
+"""Pins for the host-side planning helpers: the cost model of Sec. 3.3 against the numbers
+the paper prints for its worked example, Algorithm 2's gradient collection plan against
+the properties the paper states for it, and the C library's twins against the oracle."""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2504_19925_amd as symi
+from oracle import symi_oracle as O
+
+GB = 1e9
+# Sec. 3.3's example: GPT3-175B-sized experts, G = W = 3.375 GB, O = 27 GB, E = 64,
+# N = 2048, s = 2, host link 64 GB/s, network 400 Gbit/s
+EXAMPLE = dict(E=64, N=2048, s=2, G=3.375 * GB, W=3.375 * GB, O=27 * GB, bw_pci=64 * GB, bw_net=400e9 / 8)
+
+
+def test_cost_model_reproduces_the_printed_example():
+    c = O.comm_cost(**EXAMPLE)
+    assert c["mem_static"] == c["mem_symi"]
+    assert c["mem_symi"] / 1e12 == pytest.approx(1.7, abs=0.05)                     # "~1.7 TB per layer"
+    total = c["data_grad_symi"] + c["data_weight_symi"]
+    assert total == c["data_grad_static"] + c["data_weight_static"]
+    assert total / 1e12 == pytest.approx(27, abs=0.7)                              # "27 TB total"
+    assert c["t_grad_static"] + c["t_weight_static"] == pytest.approx(0.269, abs=5e-4)
+    assert c["t_grad_symi"] + c["t_weight_symi"] == pytest.approx(0.273, abs=5e-4)
+    assert 100 * c["extra_fraction"] == pytest.approx(1.52, abs=5e-3)              # "only 1.52 %"
+    # closed form of Sec. 3.3: (E - s) / (s N - E (1 - BW_net / BW_pci))
+    E, N, s = 64, 2048, 2
+    assert c["extra_fraction"] == pytest.approx((E - s) / (s * N - E * (1 - 50 / 64)), rel=1e-12)
+    # non-offloaded optimizer (App. A.5): (E - s) / (s N - E) = 1.54 %
+    c2 = O.comm_cost(**{**EXAMPLE, "bw_pci": float("inf")})
+    assert 100 * c2["extra_fraction"] == pytest.approx(1.54, abs=5e-3)
+    assert c2["extra_fraction"] == pytest.approx((E - s) / (s * N - E), rel=1e-12)
+
+
+def test_data_volume_does_not_depend_on_the_placement():
+    rng = np.random.default_rng(0)
+    E, N, s = 16, 8, 4
+    for _ in range(20):
+        counts, _, _ = O.place(rng.multinomial(5000, rng.dirichlet(np.full(E, 0.3))), s * N)
+        c = O.comm_cost(E, N, s, 7.0, 5.0, 40.0, 64.0, 50.0, placement_counts=counts)
+        assert c["data_grad_symi"] == pytest.approx(s * N * 7.0, rel=1e-12)
+        assert c["data_weight_symi"] == pytest.approx(s * N * 5.0, rel=1e-12)
+
+
+def _random_placement(rng, E, S):
+    return O.place(rng.multinomial(3000, rng.dirichlet(np.full(E, 0.3))), S)[1]
+
+
+def test_get_source_properties():
+    rng = np.random.default_rng(1)
+    for _ in range(30):
+        N = int(rng.choice([2, 4, 8, 16])); s = int(rng.integers(1, 5)); S = N * s
+        E = int(rng.integers(1, S + 1))
+        pl = _random_placement(rng, E, S)
+        for e in range(E):
+            hosts = O.hosts_of(pl, N, e)
+            assert hosts == sorted({q // s for q in range(S) if pl[q] == e}) and hosts
+            srcs = [O.get_source(pl, N, e, r) for r in range(N)]
+            assert all(x in hosts for x in srcs)                       # the source owns a replica
+            assert all(srcs[r] == r for r in hosts)                    # local communication first
+            remote = [srcs[r] for r in range(N) if r not in hosts]
+            if remote:                                                 # round robin over the hosts
+                load = [remote.count(h) for h in hosts]
+                assert max(load) - min(load) <= max(1, len(hosts))     # no host is singled out
+                assert all(srcs[r] == hosts[r % len(hosts)] for r in range(N) if r not in hosts)
+        # every (class, destination) pair is sent exactly once, by the rank the receiver expects
+        sent = {}
+        for rank in range(N):
+            recv, send = O.collect_grads(pl, N, E, rank)
+            assert set(recv) == set(range(E)) and all(v[1] == rank for v in recv.values())
+            for e, lst in send.items():
+                for dst, part in lst:
+                    assert dst == part and (e, dst) not in sent
+                    sent[(e, dst)] = rank
+        assert len(sent) == E * N
+        for rank in range(N):
+            recv, _ = O.collect_grads(pl, N, E, rank)
+            assert all(sent[(e, rank)] == recv[e][0] for e in range(E))
+
+
+def test_paper_example_of_intra_rank_replication_is_plannable():
+    # Sec. 4.1's example: 8 ranks, 2 slots each, 4 classes with 5, 5, 4, 2 instances
+    pl = np.repeat(np.arange(4), [5, 5, 4, 2])
+    assert O.hosts_of(pl, 8, 0) == [0, 1, 2] and O.hosts_of(pl, 8, 1) == [2, 3, 4]
+    assert O.hosts_of(pl, 8, 2) == [5, 6] and O.hosts_of(pl, 8, 3) == [7]
+    assert [O.get_source(pl, 8, 3, r) for r in range(8)] == [7] * 8
+    assert [O.get_source(pl, 8, 2, r) for r in range(8)] == [5, 6, 5, 6, 5, 5, 6, 6]
+
+
+def test_rank_group_enumeration():
+    for N in (2, 3, 8, 33):
+        seen = [O.rank_group(N, a, b) for a in range(N) for b in range(a + 1, N)]
+        assert seen == list(range(N * (N - 1) // 2))                   # N(N-1)/2 groups, Sec. 4.2
+        for a in range(N):
+            for b in range(a + 1, N):
+                assert symi.symi_rank_group(N, a, b) == O.rank_group(N, a, b)
+    for bad in ((4, 2, 2), (4, 3, 1), (4, -1, 2), (4, 0, 4)):
+        with pytest.raises(symi.SymiError):
+            symi.symi_rank_group(*bad)
+
+
+def test_library_twins_match_the_oracle():
+    rnd = random.Random(3)
+    rng = np.random.default_rng(3)
+    for _ in range(40):
+        N = rnd.choice([1, 2, 4, 8, 16]); s = rnd.randint(1, 6); S = N * s
+        E = rnd.randint(1, S)
+        pl = _random_placement(rng, E, S).astype(np.int32)
+        cfg = symi.SymiCfg.make(T=16, E=E, k=1, d=64, f=64, S_tot=S, N=N, shard=0, dtype="f32")
+        plt = torch.from_numpy(pl.copy())
+        for rank in range(N):
+            recv_src = torch.empty(E, dtype=torch.int32)
+            off = torch.empty(E + 1, dtype=torch.int32)
+            dst = torch.empty(E * N, dtype=torch.int32)
+            n = symi.symi_collect_grads(cfg, plt, rank, recv_src, off, dst)
+            recv, send = O.collect_grads(pl, N, E, rank)
+            assert recv_src.tolist() == [recv[e][0] for e in range(E)]
+            assert off[E] == n == sum(len(v) for v in send.values())
+            for e in range(E):
+                got = dst[off[e]:off[e + 1]].tolist()
+                assert got == [d for d, _ in send.get(e, [])]
+            e = rnd.randrange(E)
+            assert symi.symi_grad_source(cfg, plt, e, rank) == O.get_source(pl, N, e, rank)
+        with pytest.raises(symi.SymiError):
+            symi.symi_grad_source(cfg, plt, E, 0)
+    got = symi.symi_comm_cost(**EXAMPLE)
+    want = O.comm_cost(**EXAMPLE)
+    for k, v in want.items():
+        assert got[k] == pytest.approx(v, rel=1e-12), k
+    got = symi.symi_comm_cost(**{**EXAMPLE, "bw_pci": float("inf")})
+    want = O.comm_cost(**{**EXAMPLE, "bw_pci": float("inf")})
+    for k, v in want.items():
+        assert got[k] == pytest.approx(v, rel=1e-12), k
+    with pytest.raises(symi.SymiError):
+        symi.symi_comm_cost(E=64, N=8, s=2, G=1, W=1, O=1, bw_pci=1, bw_net=1)   # s*N < E
