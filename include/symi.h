@@ -171,6 +171,24 @@ int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp, const float*
                           const int32_t* first_slot_next, void* W1_slots, void* W2_slots,
                           void* stream);
 
+/* The replica gradient path as the paper draws it (Sec. 4.1, Fig. 7), as an alternative to
+ * symi_expert_bwd's fused per-class sum.  symi_expert_bwd_slots is symi_expert_bwd with one
+ * weight gradient per replica SLOT, summed over that slot's own rows only:
+ *   dW1_slot [S_tot,2f,d], dW2_slot [S_tot,d,f] f32 out (a slot without rows gets zeros).  */
+int symi_expert_bwd_slots(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
+                          const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
+                          const void* W1_slots, const void* W2_slots, void* dXp, float* dW1_slot,
+                          float* dW2_slot, void* ws, void* stream);
+
+/* The intra-rank part of the inter+intra-rank all-reduce (Sec. 4.1 steps 1 and 3; step 2,
+ * the exchange between ranks, has nothing to do on one GPU): for every class the first of
+ * its slots is the representative, the class's other slots add their tensor to it in slot
+ * order, the sum is multiplied by `scale` (the paper "normalizes" without stating the
+ * divisor: pass 1 for the plain sum, 1/r or 1/N for an average) and copied to all of the
+ * class's slots.  In place on dW1_slot [S_tot,2f,d], dW2_slot [S_tot,d,f] f32.          */
+int symi_replica_allreduce(const symi_cfg* cfg, const int32_t* first_slot, float scale,
+                           float* dW1_slot, float* dW2_slot, void* stream);
+
 /* ---- host helpers for the multi-rank part of the method (no GPU work; all pointers HOST).
  * Slot q of a placement lives on rank q / s, s = S_tot / N (S_tot must divide by N). */
 

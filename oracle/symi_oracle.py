@@ -17,6 +17,8 @@ What each function follows
   moe_forward       Sec. 2.1: Y[t] = sum_j gate[t,j] * FFN_{idx[t,j]}(X[t]), SwiGLU FFN
   moe_backward      the derivative of that definition (Sec. 3.2 step 3 only changes
                     where the class gradient is summed, not its value)
+  slot_gradients, replica_allreduce   Sec. 4.1 (Fig. 7): per-slot gradients, then
+                    add into the representative slot, scale, copy back
   get_source, collect_grads     App. A.4, Algorithm 2 (gradient collection plan), Sec. 4.3
   rank_group        Sec. 4.2 (groups of consecutive ranks)
   comm_cost         Sec. 3.3 (I)-(III), App. A.5: memory, data volume, communication time
@@ -309,6 +311,44 @@ def moe_backward(X, idx, gate, W1, W2, dY):
             dW1[e, f:] += dv.T @ x
             dX[sel] += du @ Wg + dv @ Wu
     return dX, dW1, dW2, dgate
+
+
+def slot_gradients(X, idx, gate, W1, W2, dY, row_of_assign, slot_offsets):
+    """Weight gradient of every replica slot on its own: slot q holds the assignments whose
+    row lies in [slot_offsets[q], slot_offsets[q+1]); its gradient is moe_backward's class
+    gradient restricted to them.  Returns dW1 [S_tot,2f,d], dW2 [S_tot,d,f] (fp64)."""
+    T, k = idx.shape
+    S_tot = len(slot_offsets) - 1
+    E, f = W1.shape[0], W2.shape[2]
+    d = W2.shape[1]
+    roa = np.asarray(row_of_assign).reshape(T, k)
+    g1 = np.zeros((S_tot, 2 * f, d), dtype=F64)
+    g2 = np.zeros((S_tot, d, f), dtype=F64)
+    for q in range(S_tot):
+        lo, hi = int(slot_offsets[q]), int(slot_offsets[q + 1])
+        if hi == lo:
+            continue
+        mine = (roa >= lo) & (roa < hi)
+        _, dW1, dW2, _ = moe_backward(X, idx, np.asarray(gate, dtype=F64) * mine, W1, W2, dY)
+        e = int(idx[mine][0])                      # all rows of a slot belong to one class
+        g1[q], g2[q] = dW1[e], dW2[e]
+    return g1, g2
+
+
+def replica_allreduce(g_slot, first_slot, scale=1.0):
+    """Sec. 4.1 steps 1 and 3 on one rank: per class, the slots after the representative (the
+    class's first slot) add their tensor to it, the sum is scaled ("normalized") and copied to
+    every slot of the class.  Returns a new array."""
+    out = np.array(g_slot, dtype=F64)
+    for e in range(len(first_slot) - 1):
+        q0, q1 = int(first_slot[e]), int(first_slot[e + 1])
+        rep = out[q0].copy()
+        for q in range(q0 + 1, q1):
+            rep += out[q]
+        rep *= scale
+        for q in range(q0, q1):
+            out[q] = rep
+    return out
 
 
 # ---------------------------------------------------------------------------- Adam

@@ -19,7 +19,8 @@ EXPORTS = [
     "symi_dispatch_capacity", "symi_dispatch_bwd", "symi_expert_fwd",
     "symi_expert_bwd", "symi_combine", "symi_combine_bwd", "symi_adam_to_replicas",
     "symi_timing_enable", "symi_timing_reset", "symi_timing_read", "symi_kernel_count",
-    "symi_kernel_name", "symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost",
+    "symi_kernel_name", "symi_expert_bwd_slots", "symi_replica_allreduce",
+    "symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost",
 ]
 
 
@@ -89,6 +90,8 @@ def lib():
             "symi_dispatch_bwd": [cfgp, vp, ip, vp, vp],
             "symi_expert_fwd": [cfgp, vp, ip, vp, vp, vp, vp, vp, vp, vp],
             "symi_expert_bwd": [cfgp, vp, vp, vp, vp, ip, ip, vp, vp, vp, fp, fp, vp, vp],
+            "symi_expert_bwd_slots": [cfgp, vp, vp, vp, vp, ip, ip, vp, vp, vp, fp, fp, vp, vp],
+            "symi_replica_allreduce": [cfgp, ip, ctypes.c_float, fp, fp, vp],
             "symi_combine": [cfgp, vp, ip, fp, vp, vp],
             "symi_combine_bwd": [cfgp, vp, vp, ip, fp, vp, fp, vp],
             "symi_adam_to_replicas": [cfgp, ctypes.POINTER(SymiAdam), fp, fp, fp, fp, fp, ip, vp, vp, vp],
@@ -102,7 +105,8 @@ def lib():
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
         L.symi_rank_group.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.symi_comm_cost.argtypes = [ctypes.POINTER(SymiCostIn), ctypes.POINTER(SymiCostOut)]
-        for name in ("symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost"):
+        for name in ("symi_expert_bwd_slots", "symi_replica_allreduce",
+    "symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost"):
             getattr(L, name).restype = ctypes.c_int
         L.symi_workspace_bytes.argtypes = [cfgp]
         L.symi_workspace_bytes.restype = ctypes.c_size_t
@@ -318,6 +322,28 @@ def symi_expert_bwd(cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots, W2_
         _dev(W2_slots, dt, "W2_slots", nw), _dev(dXp, dt, "dXp", cfg.A * cfg.d),
         _dev(dW1_class, F32, "dW1_class", 2 * ne), _dev(dW2_class, F32, "dW2_class", ne),
         _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), "symi_expert_bwd")
+
+
+def symi_expert_bwd_slots(cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots, W2_slots, dXp,
+                          dW1_slot, dW2_slot, ws):
+    dt = cfg.torch_dtype
+    nw = cfg.S_tot * cfg.d * cfg.f
+    _check(lib().symi_expert_bwd_slots(
+        ctypes.byref(cfg), _dev(dYp, dt, "dYp", cfg.A * cfg.d), _dev(Xp, dt, "Xp", cfg.A * cfg.d),
+        _dev(UV, dt, "UV", cfg.A * 2 * cfg.f), _dev(H, dt, "H", cfg.A * cfg.f),
+        _dev(slot_offsets, I32, "slot_offsets", cfg.S_tot + 1),
+        _dev(first_slot, I32, "first_slot", cfg.E + 1), _dev(W1_slots, dt, "W1_slots", 2 * nw),
+        _dev(W2_slots, dt, "W2_slots", nw), _dev(dXp, dt, "dXp", cfg.A * cfg.d),
+        _dev(dW1_slot, F32, "dW1_slot", 2 * nw), _dev(dW2_slot, F32, "dW2_slot", nw),
+        _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), "symi_expert_bwd_slots")
+
+
+def symi_replica_allreduce(cfg, first_slot, scale, dW1_slot, dW2_slot):
+    nw = cfg.S_tot * cfg.d * cfg.f
+    _check(lib().symi_replica_allreduce(
+        ctypes.byref(cfg), _dev(first_slot, I32, "first_slot", cfg.E + 1), ctypes.c_float(scale),
+        _dev(dW1_slot, F32, "dW1_slot", 2 * nw), _dev(dW2_slot, F32, "dW2_slot", nw), _stream()),
+        "symi_replica_allreduce")
 
 
 def symi_combine(cfg, Yp, row_of_assign, gate, Y):

@@ -45,6 +45,7 @@ struct GemmParams {
   int K;   // reduction length when fixed
   int d, f;
   const int32_t* class_order;   // weight gradients: classes by decreasing row count
+  int per_slot;                 // weight gradients: one output per slot instead of per class
 };
 
 __device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
@@ -177,11 +178,16 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   } else {
     // classes in order of decreasing row count: the long reductions start first and the
     // short (or empty, store-only) tiles fill in behind them
-    group = p.class_order[blockIdx.z];
+    group = p.per_slot ? blockIdx.z : p.class_order[blockIdx.z];
     row0 = blockIdx.y * BM;
     row1 = min(p.M, row0 + BM);
-    kbeg = p.slot_offsets[p.first_slot[group]];
-    K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
+    if (p.per_slot) {   // the rows of one replica slot
+      kbeg = p.slot_offsets[group];
+      K = p.slot_offsets[group + 1] - kbeg;
+    } else {            // the rows of all replica slots of a class
+      kbeg = p.slot_offsets[p.first_slot[group]];
+      K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
+    }
   }
   // FWD1: a tile holds 128 hidden units; every 64 tile columns are 32 gate columns
   // followed by the 32 up columns of the same hidden units.
@@ -580,8 +586,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
     group = blockIdx.z;
     row0 = blockIdx.y * FB;
     row1 = min(p.M, row0 + FB);
-    kbeg = p.slot_offsets[p.first_slot[group]];
-    K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
+    if (p.per_slot) {
+      kbeg = p.slot_offsets[group];
+      K = p.slot_offsets[group + 1] - kbeg;
+    } else {
+      kbeg = p.slot_offsets[p.first_slot[group]];
+      K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
+    }
   }
   const int n0 = blockIdx.x * (MODE == FWD1 ? FB / 2 : FB);
   const float* A = static_cast<const float*>(p.A);
@@ -695,11 +706,11 @@ static void launch_gemm(const symi_cfg* cfg, const GemmParams& p, int n_cols, in
                         hipStream_t st) {
   if (cfg->dtype == SYMI_BF16) {
     const int bn = MODE == FWD1 ? BN / 2 : BN;
-    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? max_mtiles : cdiv(p.M, BM), MODE <= BWD_DX ? 1 : cfg->E);
+    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? max_mtiles : cdiv(p.M, BM), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
     SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_bf16_kernel<MODE><<<grid, GT, 0, st>>>(p)));
   } else {
     const int bn = MODE == FWD1 ? FB / 2 : FB;
-    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 4 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : cfg->E);
+    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 4 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
     SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_f32_kernel<MODE><<<grid, 256, 0, st>>>(p)));
   }
 }
@@ -740,16 +751,17 @@ extern "C" int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_
   return SYMI_OK;
 }
 
-extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
-                               const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
-                               const void* W1_slots, const void* W2_slots, void* dXp,
-                               float* dW1_class, float* dW2_class, void* ws, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_expert_bwd")) return rc;
+// per_slot = false: dW1_out / dW2_out are per class (all replica slots summed in the GEMM);
+// per_slot = true: one gradient per replica slot (its own rows only)
+static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp, const void* Xp,
+                           const void* UV, const void* H, const int32_t* slot_offsets,
+                           const int32_t* first_slot, const void* W1_slots, const void* W2_slots,
+                           void* dXp, float* dW1_class, float* dW2_class, void* ws, void* stream,
+                           bool per_slot) {
+  if (int rc = check_cfg(cfg, who)) return rc;
   const long long A = (long long)cfg->T * cfg->k;
-  SYMI_REQUIRE(slot_offsets && first_slot && dW1_class && dW2_class && ws, "symi_expert_bwd",
-               "NULL pointer");
-  SYMI_REQUIRE(A == 0 || (dYp && Xp && UV && H && W1_slots && W2_slots && dXp), "symi_expert_bwd",
-               "NULL pointer");
+  SYMI_REQUIRE(slot_offsets && first_slot && dW1_class && dW2_class && ws, who, "NULL pointer");
+  SYMI_REQUIRE(A == 0 || (dYp && Xp && UV && H && W1_slots && W2_slots && dXp), who, "NULL pointer");
   hipStream_t st = as_stream(stream);
   const WsLayout L = ws_layout(cfg);
   int32_t* map = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.tile_map);
@@ -762,6 +774,7 @@ extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void*
   p.slot_offsets = slot_offsets;
   p.first_slot = first_slot;
   p.class_order = order;
+  p.per_slot = per_slot ? 1 : 0;
   p.d = cfg->d;
   p.f = cfg->f;
   SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, first_slot, cfg->S_tot, cfg->E, map, order)));
@@ -795,6 +808,61 @@ extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void*
   p.c_group_stride = 2LL * cfg->f * cfg->d;
   p.M = 2 * cfg->f; p.N = cfg->d;
   launch_gemm<WGRAD1>(cfg, p, cfg->d, 0, st);
-  SYMI_LAUNCH_CHECK("symi_expert_bwd");
+  SYMI_LAUNCH_CHECK(who);
+  return SYMI_OK;
+}
+
+extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
+                               const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
+                               const void* W1_slots, const void* W2_slots, void* dXp,
+                               float* dW1_class, float* dW2_class, void* ws, void* stream) {
+  return expert_bwd_impl("symi_expert_bwd", cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots,
+                         W2_slots, dXp, dW1_class, dW2_class, ws, stream, false);
+}
+
+extern "C" int symi_expert_bwd_slots(const symi_cfg* cfg, const void* dYp, const void* Xp,
+                                     const void* UV, const void* H, const int32_t* slot_offsets,
+                                     const int32_t* first_slot, const void* W1_slots,
+                                     const void* W2_slots, void* dXp, float* dW1_slot,
+                                     float* dW2_slot, void* ws, void* stream) {
+  return expert_bwd_impl("symi_expert_bwd_slots", cfg, dYp, Xp, UV, H, slot_offsets, first_slot,
+                         W1_slots, W2_slots, dXp, dW1_slot, dW2_slot, ws, stream, true);
+}
+
+// ---------------------------------------------------------------- replica all-reduce
+// The intra-rank part of the paper's all-reduce (Sec. 4.1): for every class the first of its
+// slots is the representative; the other slots add their gradient to it (slot order), the
+// sum is scaled and copied back to all of them.  16 bytes per lane, one class per blockIdx.y.
+namespace symi {
+__global__ __launch_bounds__(256) void replica_allreduce_kernel(float4* __restrict__ g,
+                                                                const int32_t* __restrict__ first_slot,
+                                                                long long n4, float scale) {
+  const int e = blockIdx.y;
+  const int q0 = first_slot[e], q1 = first_slot[e + 1];
+  if (q1 - q0 == 1 && scale == 1.f) return;   // a single replica: nothing to exchange
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long long)gridDim.x * 256) {
+    float4 a = g[(long long)q0 * n4 + i];
+    for (int q = q0 + 1; q < q1; ++q) {
+      const float4 b = g[(long long)q * n4 + i];
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    a.x *= scale; a.y *= scale; a.z *= scale; a.w *= scale;
+    for (int q = q0; q < q1; ++q) g[(long long)q * n4 + i] = a;
+  }
+}
+}  // namespace symi
+
+extern "C" int symi_replica_allreduce(const symi_cfg* cfg, const int32_t* first_slot, float scale,
+                                      float* dW1_slot, float* dW2_slot, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_replica_allreduce")) return rc;
+  SYMI_REQUIRE(first_slot && dW1_slot && dW2_slot, "symi_replica_allreduce", "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  const long long n1 = 2LL * cfg->f * cfg->d / 4, n2 = (long long)cfg->d * cfg->f / 4;
+  auto blocks = [](long long n4) { long long b = (n4 + 255) / 256; return (unsigned)(b > 2048 ? 2048 : (b < 1 ? 1 : b)); };
+  SYMI_TIMED(K_REPLICA_AR, st, (replica_allreduce_kernel<<<dim3(blocks(n1), cfg->E), 256, 0, st>>>(
+      reinterpret_cast<float4*>(dW1_slot), first_slot, n1, scale)));
+  SYMI_TIMED(K_REPLICA_AR, st, (replica_allreduce_kernel<<<dim3(blocks(n2), cfg->E), 256, 0, st>>>(
+      reinterpret_cast<float4*>(dW2_slot), first_slot, n2, scale)));
+  SYMI_LAUNCH_CHECK("symi_replica_allreduce");
   return SYMI_OK;
 }
