@@ -60,7 +60,7 @@ typedef struct symi_adam {
 /* Host-only checks of a configuration (no GPU needed). */
 int symi_validate(const symi_cfg* cfg);
 /* Bytes of device workspace `ws` that symi_dispatch / symi_expert_fwd /
- * symi_expert_bwd need for this configuration (0 if cfg is invalid). */
+ * symi_expert_bwd / symi_router_bwd need for this configuration (0 if cfg is invalid). */
 size_t symi_workspace_bytes(const symi_cfg* cfg);
 const char* symi_last_error(void);
 
@@ -170,6 +170,20 @@ int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp, const float*
                           const float* dW2_class, float* master_w, float* m, float* v,
                           const int32_t* first_slot_next, void* W1_slots, void* W2_slots,
                           void* stream);
+
+/* The gate network in front of symi_route (Sec. 2.1: a learned router scores every token
+ * against every expert class), so that the layer is closed from X to dX:
+ *   logits [T,E] f32 out = X Wr^T + b.   X [T,d], Wr [E,d] in the activation dtype (row e of
+ *   Wr is class e's scoring vector), b [E] f32 or NULL.                                   */
+int symi_router_fwd(const symi_cfg* cfg, const void* X, const void* Wr, const float* b,
+                    float* logits, void* stream);
+
+/* Backward of symi_router_fwd from dlogits [T,E] f32 (symi_route_bwd's output):
+ *   dWr [E,d] f32 out = dlogits^T X;  db [E] f32 out = column sums of dlogits (NULL: skipped);
+ *   dX [T,d] IN/OUT: dlogits Wr is ADDED to it (call after symi_dispatch_bwd).
+ * Deterministic: the reduction over tokens is cut into fixed chunks summed in order.      */
+int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* Wr, const float* dlogits,
+                    float* dWr, float* db, void* dX, void* ws, void* stream);
 
 /* The replica gradient path as the paper draws it (Sec. 4.1, Fig. 7), as an alternative to
  * symi_expert_bwd's fused per-class sum.  symi_expert_bwd_slots is symi_expert_bwd with one

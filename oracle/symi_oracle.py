@@ -7,6 +7,7 @@ imports nothing from the HIP package.  Library primitives used as steps: numpy's
 stable sort and matmul.
 
 What each function follows
+  router_forward, router_backward   Sec. 2.1: the learned gate network (a linear layer)
   route             Sec. 2.1 (top-k gating) and Sec. 3.2 step 1 (per-class token count)
   place             Appendix A.3, Algorithm 1 (Expert Placement Scheduler), Sec. 3.4
   place_float_literal   the same listing evaluated in binary64 as printed (a second
@@ -41,6 +42,19 @@ Readings where the paper is silent (each is stated at its function):
 import numpy as np
 
 F64 = np.float64
+
+
+# -------------------------------------------------------------------------- router
+def router_forward(X, Wr, b=None):
+    """logits[t,e] = <X[t], Wr[e]> + b[e]  (Sec. 2.1: the learned router), fp64."""
+    z = np.asarray(X, dtype=F64) @ np.asarray(Wr, dtype=F64).T
+    return z if b is None else z + np.asarray(b, dtype=F64)[None, :]
+
+
+def router_backward(X, Wr, dlogits):
+    """Gradients of the linear router: dWr = dlogits^T X, db = column sums, dX = dlogits Wr."""
+    dl = np.asarray(dlogits, dtype=F64)
+    return dl.T @ np.asarray(X, dtype=F64), dl.sum(axis=0), dl @ np.asarray(Wr, dtype=F64)
 
 
 # --------------------------------------------------------------------------- route

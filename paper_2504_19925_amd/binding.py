@@ -19,7 +19,7 @@ EXPORTS = [
     "symi_dispatch_capacity", "symi_dispatch_bwd", "symi_expert_fwd",
     "symi_expert_bwd", "symi_combine", "symi_combine_bwd", "symi_adam_to_replicas",
     "symi_timing_enable", "symi_timing_reset", "symi_timing_read", "symi_kernel_count",
-    "symi_kernel_name", "symi_expert_bwd_slots", "symi_replica_allreduce",
+    "symi_kernel_name", "symi_expert_bwd_slots", "symi_replica_allreduce", "symi_router_fwd", "symi_router_bwd",
     "symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost",
 ]
 
@@ -92,6 +92,8 @@ def lib():
             "symi_expert_bwd": [cfgp, vp, vp, vp, vp, ip, ip, vp, vp, vp, fp, fp, vp, vp],
             "symi_expert_bwd_slots": [cfgp, vp, vp, vp, vp, ip, ip, vp, vp, vp, fp, fp, vp, vp],
             "symi_replica_allreduce": [cfgp, ip, ctypes.c_float, fp, fp, vp],
+            "symi_router_fwd": [cfgp, vp, vp, fp, fp, vp],
+            "symi_router_bwd": [cfgp, vp, vp, fp, fp, fp, vp, vp, vp],
             "symi_combine": [cfgp, vp, ip, fp, vp, vp],
             "symi_combine_bwd": [cfgp, vp, vp, ip, fp, vp, fp, vp],
             "symi_adam_to_replicas": [cfgp, ctypes.POINTER(SymiAdam), fp, fp, fp, fp, fp, ip, vp, vp, vp],
@@ -105,7 +107,7 @@ def lib():
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
         L.symi_rank_group.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.symi_comm_cost.argtypes = [ctypes.POINTER(SymiCostIn), ctypes.POINTER(SymiCostOut)]
-        for name in ("symi_expert_bwd_slots", "symi_replica_allreduce",
+        for name in ("symi_expert_bwd_slots", "symi_replica_allreduce", "symi_router_fwd", "symi_router_bwd",
     "symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost"):
             getattr(L, name).restype = ctypes.c_int
         L.symi_workspace_bytes.argtypes = [cfgp]
@@ -344,6 +346,23 @@ def symi_replica_allreduce(cfg, first_slot, scale, dW1_slot, dW2_slot):
         ctypes.byref(cfg), _dev(first_slot, I32, "first_slot", cfg.E + 1), ctypes.c_float(scale),
         _dev(dW1_slot, F32, "dW1_slot", 2 * nw), _dev(dW2_slot, F32, "dW2_slot", nw), _stream()),
         "symi_replica_allreduce")
+
+
+def symi_router_fwd(cfg, X, Wr, b, logits):
+    dt = cfg.torch_dtype
+    _check(lib().symi_router_fwd(
+        ctypes.byref(cfg), _dev(X, dt, "X", cfg.T * cfg.d), _dev(Wr, dt, "Wr", cfg.E * cfg.d),
+        None if b is None else _dev(b, F32, "b", cfg.E), _dev(logits, F32, "logits", cfg.T * cfg.E),
+        _stream()), "symi_router_fwd")
+
+
+def symi_router_bwd(cfg, X, Wr, dlogits, dWr, db, dX, ws):
+    dt = cfg.torch_dtype
+    _check(lib().symi_router_bwd(
+        ctypes.byref(cfg), _dev(X, dt, "X", cfg.T * cfg.d), _dev(Wr, dt, "Wr", cfg.E * cfg.d),
+        _dev(dlogits, F32, "dlogits", cfg.T * cfg.E), _dev(dWr, F32, "dWr", cfg.E * cfg.d),
+        None if db is None else _dev(db, F32, "db", cfg.E), _dev(dX, dt, "dX", cfg.T * cfg.d),
+        _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), "symi_router_bwd")
 
 
 def symi_combine(cfg, Yp, row_of_assign, gate, Y):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsymi.so")
-SOURCES = ["api.hip", "route.hip", "place.hip", "dispatch.hip", "gemm.hip", "adam.hip", "comm_plan.hip"]
+SOURCES = ["api.hip", "route.hip", "place.hip", "dispatch.hip", "gemm.hip", "adam.hip", "comm_plan.hip", "router.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -66,6 +66,8 @@ WsLayout ws_layout(const symi_cfg* c) {
   off += align_up(A * 2 * c->f * w, 256);
   L.dh = off;
   off += align_up(A * c->f * w, 256);
+  L.router_partial = off;
+  off += align_up(((size_t)c->T + 2047) / 2048 * c->E * c->d * sizeof(float), 256);
   L.total = off + 256;
   return L;
 }
@@ -79,7 +81,7 @@ static const char* const g_names[K_COUNT] = {
     "fill_i32", "route", "route_bwd", "place", "chunk_count", "chunk_scan", "chunk_rank",
     "gather_rows", "tile_map", "gemm_fwd1", "gemm_fwd2", "gemm_bwd_dh", "gemm_bwd_dx",
     "gemm_wgrad2", "gemm_wgrad1", "combine", "combine_bwd", "dispatch_bwd", "adam_to_replicas",
-    "dswiglu", "replica_allreduce"};
+    "dswiglu", "replica_allreduce", "router_fwd", "router_dx", "router_dw"};
 
 void timing_begin(int kid, hipStream_t st) {
   hipEvent_t e;

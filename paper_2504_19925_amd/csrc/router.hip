@@ -1,0 +1,294 @@
+// symi_router_fwd / symi_router_bwd: the learned gate network in front of symi_route
+// (paper Sec. 2.1: the router scores every token against every expert class):
+//   logits = X Wr^T + b          dWr = dlogits^T X,  db = sum_t dlogits,  dX += dlogits Wr
+// Three skinny products (one side is E <= 1024 wide) that share one small tiled kernel:
+// 128 x 128 output tile, 4 wavefronts of 64 x 64 (2 x 2 MFMA 32x32x16 bf16 tiles), reduction
+// step 32.  Operands pass through registers into LDS (rows padded to 80 bytes) so that either
+// side may be reduction-contiguous (16-byte loads) or reduction-strided (8 coalesced
+// scalar loads), bf16 or fp32 in memory; many workgroups per compute unit hide the latency.
+// The weight gradient's reduction runs over all T tokens: it is cut into chunks of 2048
+// tokens whose partial products are summed by a second kernel in a fixed order.
+// fp32 configurations take a plain FMA kernel (one output per thread) instead.
+#include "common.h"
+
+namespace symi {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 rbf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float rfloatx16;
+
+constexpr int RT = 128;        // tile rows and columns
+constexpr int RK = 32;         // reduction step
+constexpr int RLD = RK + 8;    // padded LDS row (elements)
+constexpr int RCHUNK = 2048;   // tokens per partial weight gradient
+
+enum { R_FWD = 0, R_DX = 1, R_DW = 2 };
+
+struct RouterParams {
+  const void* X;        // [T,d] activations (bf16)
+  const void* Wr;       // [E,d] router weights (bf16)
+  const float* b;       // [E] or null
+  const float* dl;      // [T,E] dlogits
+  float* logits;        // [T,E]
+  void* dX;             // [T,d] accumulated into
+  float* partial;       // [nchunk,E,d]
+  int T, E, d;
+};
+
+__device__ __forceinline__ uint4 pack8(const float (&v)[8]) {
+  return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                    pack_bf16x2(v[6], v[7]));
+}
+
+// 8 consecutive reduction indices k..k+7 of operand row `r`, as bf16, zero outside.
+//   contiguous bf16:  src[r*ld + k ..]            strided bf16:  src[(k+i)*ld + r]
+//   contiguous fp32:  src[r*ld + k ..] converted  strided fp32:  src[(k+i)*ld + r] converted
+template <bool CONTIG, bool F32>
+__device__ __forceinline__ uint4 load8(const void* src, long long ld, int r, int rows, int k, int kend) {
+  if (r >= rows || k >= kend) return make_uint4(0, 0, 0, 0);
+  float v[8];
+  if (CONTIG && !F32 && k + 8 <= kend) {
+    return *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src) + (long long)r * ld + k);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const long long at = CONTIG ? (long long)r * ld + k + i : (long long)(k + i) * ld + r;
+    if (k + i < kend)
+      v[i] = F32 ? static_cast<const float*>(src)[at] : bf16_to_f32(static_cast<const uint16_t*>(src)[at]);
+    else
+      v[i] = 0.f;
+  }
+  return pack8(v);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
+  __shared__ __attribute__((aligned(16))) uint16_t As[RT * RLD];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[RT * RLD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // output rows M, columns N, reduction range [kbeg, kend)
+  const int M = MODE == R_DW ? p.E : p.T;
+  const int N = MODE == R_FWD ? p.E : p.d;
+  const int m0 = blockIdx.y * RT, n0 = blockIdx.x * RT;
+  int kbeg = 0, kend = MODE == R_FWD ? p.d : MODE == R_DX ? p.E : p.T;
+  if (MODE == R_DW) {
+    kbeg = blockIdx.z * RCHUNK;
+    kend = min(p.T, kbeg + RCHUNK);
+  }
+  rfloatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  for (int k0 = kbeg; k0 < kend; k0 += RK) {
+    // fill: 128 rows x 4 pieces of 8 per operand, two per thread.  Reduction-contiguous
+    // operands walk a row with consecutive threads, strided ones walk the rows.
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int u = tid + 256 * h;
+      {
+        constexpr bool contig = MODE != R_DW;
+        const int r = contig ? u >> 2 : u & 127, piece = contig ? u & 3 : u >> 7;
+        uint4 v;
+        if (MODE == R_FWD) v = load8<true, false>(p.X, p.d, m0 + r, M, k0 + 8 * piece, kend);
+        else if (MODE == R_DX) v = load8<true, true>(p.dl, p.E, m0 + r, M, k0 + 8 * piece, kend);
+        else v = load8<false, true>(p.dl, p.E, m0 + r, M, k0 + 8 * piece, kend);
+        *reinterpret_cast<uint4*>(&As[r * RLD + 8 * piece]) = v;
+      }
+      {
+        constexpr bool contig = MODE == R_FWD;
+        const int r = contig ? u >> 2 : u & 127, piece = contig ? u & 3 : u >> 7;
+        uint4 v;
+        if (MODE == R_FWD) v = load8<true, false>(p.Wr, p.d, n0 + r, N, k0 + 8 * piece, kend);
+        else if (MODE == R_DX) v = load8<false, false>(p.Wr, p.d, n0 + r, N, k0 + 8 * piece, kend);
+        else v = load8<false, false>(p.X, p.d, n0 + r, N, k0 + 8 * piece, kend);
+        *reinterpret_cast<uint4*>(&Bs[r * RLD + 8 * piece]) = v;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < RK / 16; ++ks) {
+      rbf16x8 af[2], bfr[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = *reinterpret_cast<const rbf16x8*>(&As[(wm * 64 + i * 32 + (lane & 31)) * RLD + ks * 16 + 8 * (lane >> 5)]);
+        bfr[i] = *reinterpret_cast<const rbf16x8*>(&Bs[(wn * 64 + i * 32 + (lane & 31)) * RLD + ks * 16 + 8 * (lane >> 5)]);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // a lane owns output row lane%32 of each 32 x 32 block and, per 8-column group g, the 4
+  // columns 8g + 4*(lane/32) ..
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = m0 + wm * 64 + i * 32 + (lane & 31);
+    if (row >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
+        if (col >= N) continue;
+        float x[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) x[c] = acc[i][j][4 * g + c];
+        const long long at = (long long)row * N + col;
+        if (col + 3 < N && (N & 3) == 0) {   // 4 columns at once (16 bytes fp32, 8 bytes bf16)
+          if (MODE == R_FWD) {
+            float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p.b) bb = make_float4(p.b[col], p.b[col + 1], p.b[col + 2], p.b[col + 3]);
+            *reinterpret_cast<float4*>(p.logits + at) = make_float4(x[0] + bb.x, x[1] + bb.y, x[2] + bb.z, x[3] + bb.w);
+          } else if (MODE == R_DX) {
+            uint2* o = reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.dX) + at);
+            const uint2 old = *o;
+            *o = make_uint2(pack_bf16x2(__uint_as_float(old.x << 16) + x[0], __uint_as_float(old.x & 0xffff0000u) + x[1]),
+                            pack_bf16x2(__uint_as_float(old.y << 16) + x[2], __uint_as_float(old.y & 0xffff0000u) + x[3]));
+          } else {
+            *reinterpret_cast<float4*>(p.partial + (long long)blockIdx.z * M * N + at) = make_float4(x[0], x[1], x[2], x[3]);
+          }
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            if (col + c >= N) continue;
+            if (MODE == R_FWD) {
+              p.logits[at + c] = x[c] + (p.b ? p.b[col + c] : 0.f);
+            } else if (MODE == R_DX) {
+              uint16_t* o = static_cast<uint16_t*>(p.dX) + at + c;
+              *o = f32_to_bf16(bf16_to_f32(*o) + x[c]);
+            } else {
+              p.partial[(long long)blockIdx.z * M * N + at + c] = x[c];
+            }
+          }
+        }
+      }
+  }
+}
+
+// dWr[e,n] = sum over chunks of partial[chunk,e,n], chunks in ascending order
+__global__ __launch_bounds__(256) void router_reduce_kernel(const float* __restrict__ partial, int nchunk,
+                                                            long long n, float* __restrict__ dWr) {
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+    float s = 0.f;
+    for (int c = 0; c < nchunk; ++c) s += partial[(long long)c * n + i];
+    dWr[i] = s;
+  }
+}
+
+// db[e] = sum_t dl[t,e]: one workgroup per class, fixed summation tree
+__global__ __launch_bounds__(256) void router_bias_grad_kernel(const float* __restrict__ dl, int T, int E,
+                                                               float* __restrict__ db) {
+  __shared__ float red[256];
+  const int e = blockIdx.x;
+  float s = 0.f;
+  for (int t = threadIdx.x; t < T; t += 256) s += dl[(long long)t * E + e];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o >= 1; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) db[e] = red[0];
+}
+
+// ---- fp32 configurations: one output element per thread, plain FMAs in index order
+__global__ __launch_bounds__(256) void router_fwd_f32_kernel(const float* __restrict__ X,
+                                                             const float* __restrict__ Wr,
+                                                             const float* __restrict__ b,
+                                                             float* __restrict__ logits, int T, int E, int d) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long long)T * E) return;
+  const int t = (int)(i / E), e = (int)(i - (long long)t * E);
+  float s = 0.f;
+  for (int k = 0; k < d; ++k) s = fmaf(X[(long long)t * d + k], Wr[(long long)e * d + k], s);
+  logits[i] = s + (b ? b[e] : 0.f);
+}
+__global__ __launch_bounds__(256) void router_dx_f32_kernel(const float* __restrict__ dl,
+                                                            const float* __restrict__ Wr,
+                                                            float* __restrict__ dX, int T, int E, int d) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long long)T * d) return;
+  const int t = (int)(i / d), n = (int)(i - (long long)t * d);
+  float s = 0.f;
+  for (int e = 0; e < E; ++e) s = fmaf(dl[(long long)t * E + e], Wr[(long long)e * d + n], s);
+  dX[i] += s;
+}
+__global__ __launch_bounds__(256) void router_dw_f32_kernel(const float* __restrict__ dl,
+                                                            const float* __restrict__ X,
+                                                            float* __restrict__ dWr, int T, int E, int d) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long long)E * d) return;
+  const int e = (int)(i / d), n = (int)(i - (long long)e * d);
+  // two-level sum: 16-token partial sums first (keeps the rounding error of a long
+  // reduction near sqrt(T/16) ulps)
+  float s = 0.f;
+  for (int t0 = 0; t0 < T; t0 += 16) {
+    float part = 0.f;
+    const int t1 = min(T, t0 + 16);
+    for (int t = t0; t < t1; ++t) part = fmaf(dl[(long long)t * E + e], X[(long long)t * d + n], part);
+    s += part;
+  }
+  dWr[i] = s;
+}
+
+}  // namespace symi
+
+using namespace symi;
+
+extern "C" int symi_router_fwd(const symi_cfg* cfg, const void* X, const void* Wr, const float* b,
+                               float* logits, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_router_fwd")) return rc;
+  if (cfg->T == 0) return SYMI_OK;
+  SYMI_REQUIRE(X && Wr && logits, "symi_router_fwd", "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  const int T = cfg->T, E = cfg->E, d = cfg->d;
+  if (cfg->dtype == SYMI_BF16) {
+    RouterParams p = {};
+    p.X = X; p.Wr = Wr; p.b = b; p.logits = logits; p.T = T; p.E = E; p.d = d;
+    SYMI_TIMED(K_ROUTER_FWD, st, (router_gemm_kernel<R_FWD><<<dim3(cdiv(E, RT), cdiv(T, RT)), 256, 0, st>>>(p)));
+  } else {
+    SYMI_TIMED(K_ROUTER_FWD, st, (router_fwd_f32_kernel<<<cdiv((long long)T * E, 256), 256, 0, st>>>(
+        static_cast<const float*>(X), static_cast<const float*>(Wr), b, logits, T, E, d)));
+  }
+  SYMI_LAUNCH_CHECK("symi_router_fwd");
+  return SYMI_OK;
+}
+
+extern "C" int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* Wr, const float* dlogits,
+                               float* dWr, float* db, void* dX, void* ws, void* stream) {
+  if (int rc = check_cfg(cfg, "symi_router_bwd")) return rc;
+  SYMI_REQUIRE(dWr && ws, "symi_router_bwd", "NULL pointer");
+  SYMI_REQUIRE(cfg->T == 0 || (X && Wr && dlogits && dX), "symi_router_bwd", "NULL pointer");
+  hipStream_t st = as_stream(stream);
+  const int T = cfg->T, E = cfg->E, d = cfg->d;
+  const WsLayout L = ws_layout(cfg);
+  if (cfg->dtype == SYMI_BF16) {
+    RouterParams p = {};
+    p.X = X; p.Wr = Wr; p.dl = dlogits; p.dX = dX; p.T = T; p.E = E; p.d = d;
+    p.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + L.router_partial);
+    const int nchunk = cdiv(T, RCHUNK);
+    if (T > 0) {
+      SYMI_TIMED(K_ROUTER_DX, st, (router_gemm_kernel<R_DX><<<dim3(cdiv(d, RT), cdiv(T, RT)), 256, 0, st>>>(p)));
+      SYMI_TIMED(K_ROUTER_DW, st, (router_gemm_kernel<R_DW><<<dim3(cdiv(d, RT), cdiv(E, RT), nchunk), 256, 0, st>>>(p)));
+    }
+    const long long n = (long long)E * d;
+    SYMI_TIMED(K_ROUTER_DW, st, (router_reduce_kernel<<<cdiv(n, 256), 256, 0, st>>>(p.partial, nchunk, n, dWr)));
+  } else {
+    if (T > 0)
+      SYMI_TIMED(K_ROUTER_DX, st, (router_dx_f32_kernel<<<cdiv((long long)T * d, 256), 256, 0, st>>>(
+          dlogits, static_cast<const float*>(Wr), static_cast<float*>(dX), T, E, d)));
+    SYMI_TIMED(K_ROUTER_DW, st, (router_dw_f32_kernel<<<cdiv((long long)E * d, 256), 256, 0, st>>>(
+        dlogits, static_cast<const float*>(X), dWr, T, E, d)));
+  }
+  if (db) SYMI_TIMED(K_ROUTER_DW, st, (router_bias_grad_kernel<<<E, 256, 0, st>>>(dlogits, T, E, db)));
+  SYMI_LAUNCH_CHECK("symi_router_bwd");
+  return SYMI_OK;
+}

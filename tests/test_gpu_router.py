@@ -1,0 +1,102 @@
+"""GPU parity of the router GEMM and its backward (symi_router_fwd / symi_router_bwd), alone
+and closing the layer from X to dX.  Float tolerance only: the oracle routes the GPU's own
+logits, so both sides take the same top-k decisions."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2504_19925_amd as symi
+import workloads as wl
+from oracle import symi_oracle as O
+from tests import harness as Hn
+from tests.test_gpu_parity import _small
+from tests.util import check_close, relerr_elem, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_router_closes_the_layer(name):
+    c = _small(name)
+    st = Hn.State(c)
+    X, _, dY = Hn.draw_inputs(c, 0)
+    Wr, b = wl.make_router(c, 0, "cuda")
+    logits = torch.empty(c.T, c.E, dtype=torch.float32, device="cuda")
+    symi.symi_router_fwd(st.cfg, X, Wr, b, logits)
+    Hn.sync()
+    Xn, Wn, bn, dYn = Hn.npf(X), Hn.npf(Wr), Hn.npf(b), Hn.npf(dY)
+    log = {}
+    check_close("logits", Hn.npf(logits), O.router_forward(Xn, Wn, bn), c.dtype, log=log)
+    # without bias
+    l2 = torch.empty_like(logits)
+    symi.symi_router_fwd(st.cfg, X, Wr, None, l2)
+    check_close("logits_nobias", Hn.npf(l2), O.router_forward(Xn, Wn), c.dtype, log=log)
+    # ---- the layer on the GPU's logits, then the router's backward
+    st.place_current()
+    st.forward(X, logits)
+    st.backward(dY, logits)
+    dX_experts = st.dX.clone()
+    dWr = torch.empty(c.E, c.d, dtype=torch.float32, device="cuda")
+    db = torch.empty(c.E, dtype=torch.float32, device="cuda")
+    symi.symi_router_bwd(st.cfg, X, Wr, st.dlogits, dWr, db, st.dX, st.ws)
+    Hn.sync()
+    zn = Hn.npf(logits)
+    o_idx, o_gate, _ = O.route(zn, c.k, True)
+    assert (st.idx.cpu().numpy() == o_idx).all()
+    W1n, W2n = Hn.npf(st.W1c), Hn.npf(st.W2c)
+    dX_e, _, _, dgate = O.moe_backward(Xn, o_idx, o_gate, W1n, W2n, dYn)
+    dlog = O.route_backward(zn, o_idx, o_gate, dgate, True)
+    o_dWr, o_db, o_dXr = O.router_backward(Xn, Wn, dlog)
+    check_close("dWr", Hn.npf(dWr), o_dWr, c.dtype, log=log)
+    # db sums dlogits over all tokens, with heavy cancellation (every row of dlogits sums to
+    # zero): the error the upstream bf16 stages leave in dlogits is judged against the size
+    # of the summands, not of the much smaller sum
+    db_scale = np.abs(dlog).sum(axis=0).max()
+    assert np.abs(Hn.npf(db) - o_db).max() / db_scale <= TOL["bf16" if c.dtype == "bf16" else "f32"]
+    check_close("dX_total", Hn.npf(st.dX), dX_e + o_dXr, c.dtype, log=log)
+    # stage-isolated: fed the GPU's own dlogits, db is an fp32 sum and the router's share of dX
+    # is what was added on top of the experts' dX
+    gl = Hn.npf(st.dlogits)
+    i_dWr, i_db, i_dXr = O.router_backward(Xn, Wn, gl)
+    assert relerr_elem(Hn.npf(db), i_db) <= 1e-5
+    check_close("dWr_iso", Hn.npf(dWr), i_dWr, c.dtype, log=log)
+    # the router's own share of dX, accumulated into a zeroed buffer (on top of the experts'
+    # bf16 dX it would drown in that sum's rounding)
+    dXr = torch.zeros_like(st.dX)
+    dWr2, db2 = torch.empty_like(dWr), torch.empty_like(db)
+    symi.symi_router_bwd(st.cfg, X, Wr, st.dlogits, dWr2, db2, dXr, st.ws)
+    Hn.sync()
+    check_close("dXr_iso", Hn.npf(dXr), i_dXr, c.dtype, log=log)
+    assert torch.equal(dWr2, dWr) and torch.equal(db2, db)          # deterministic
+    if c.dtype == "f32":
+        assert relerr_elem(Hn.npf(st.dX) - Hn.npf(dX_experts), i_dXr) <= 1e-4
+    print("[err] " + " ".join(f"{k}:max={v['max']:.2e}" for k, v in log.items()), flush=True)
+
+
+def test_router_full_size_sampled_c5():
+    """Config c5's full shape (T=65536, d=4096, E=128): sampled logits rows, sampled dWr
+    columns and sampled dX rows against the oracle."""
+    c = wl.get_config("c5")
+    cfg = Hn.make_cfg(c)
+    X = wl.make_tokens(c, 0, "cuda")
+    Wr, b = wl.make_router(c, 0, "cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(9)
+    dl = torch.randn(c.T, c.E, generator=g, device="cuda", dtype=torch.float32)
+    logits = torch.empty(c.T, c.E, dtype=torch.float32, device="cuda")
+    dX = torch.zeros(c.T, c.d, dtype=cfg.torch_dtype, device="cuda")
+    dWr = torch.empty(c.E, c.d, dtype=torch.float32, device="cuda")
+    db = torch.empty(c.E, dtype=torch.float32, device="cuda")
+    ws = torch.empty(symi.symi_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    symi.symi_router_fwd(cfg, X, Wr, b, logits)
+    symi.symi_router_bwd(cfg, X, Wr, dl, dWr, db, dX, ws)
+    Hn.sync()
+    rows = torch.randint(0, c.T, (64,), generator=torch.Generator().manual_seed(1)).tolist() + [0, c.T - 1]
+    Xs, Wn, bn = Hn.npf(X[rows]), Hn.npf(Wr), Hn.npf(b)
+    log = {}
+    check_close("logits", Hn.npf(logits[rows]), O.router_forward(Xs, Wn, bn), "bf16", log=log)
+    check_close("dX", Hn.npf(dX[rows]), Hn.npf(dl[rows]).astype(np.float64) @ Wn.astype(np.float64), "bf16", log=log)
+    cols = torch.randint(0, c.d, (24,), generator=torch.Generator().manual_seed(2)).tolist() + [0, c.d - 1]
+    want = Hn.npf(dl).astype(np.float64).T @ Hn.npf(X[:, cols]).astype(np.float64)
+    check_close("dWr", Hn.npf(dWr[:, cols]), want, "bf16", log=log)
+    assert relerr_elem(Hn.npf(db), Hn.npf(dl).astype(np.float64).sum(0)) <= 1e-5
+    print("[err] " + " ".join(f"{k}:max={v['max']:.2e}" for k, v in log.items()), flush=True)

@@ -13,4 +13,5 @@ from .gen import (  # noqa: F401
     make_class_weights,
     make_upstream_grad,
     bias_schedule,
+    make_router,
 )

@@ -11,7 +11,7 @@ import torch
 from .configs import Config
 
 _TENSOR_IDS = {"tokens": 1, "router_w": 2, "noise": 3, "w1": 4, "w2": 5, "dy": 6,
-               "perm": 7, "walk": 8}
+               "perm": 7, "walk": 8, "router_wr": 9}
 
 
 def _gen(cfg: Config, what: str, it: int, device) -> torch.Generator:
@@ -92,3 +92,13 @@ def make_logits(cfg: Config, it: int = 0, device="cpu", tokens: torch.Tensor = N
     noise = torch.randn(cfg.T, cfg.E, generator=_gen(cfg, "noise", it, device),
                         device=device, dtype=torch.float32)
     return (noise * cfg.noise_sigma + b).contiguous()
+
+
+def make_router(cfg: Config, it: int = 0, device="cpu"):
+    """Router parameters for the closed layer: Wr [E, d] ~ N(0, 0.02^2) in the config's
+    activation dtype (row e scores class e), b [E] fp32 = the popularity bias of iteration
+    `it` (so the routed histogram keeps the config's skew)."""
+    wr = torch.randn(cfg.E, cfg.d, generator=_gen(cfg, "router_wr", 0, device), device=device,
+                     dtype=torch.float32) * 0.02
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    return wr.to(dt).contiguous(), bias_schedule(cfg, it).to(device).to(torch.float32).contiguous()
