@@ -67,7 +67,9 @@ WsLayout ws_layout(const symi_cfg* c) {
   L.dh = off;
   off += align_up(A * c->f * w, 256);
   L.router_partial = off;
-  off += align_up(((size_t)c->T + 2047) / 2048 * c->E * c->d * sizeof(float), 256);
+  off += align_up(((size_t)c->T + 511) / 512 * c->E * c->d * sizeof(float), 256);
+  L.router_bias_partial = off;
+  off += align_up(((size_t)c->T + 255) / 256 * c->E * sizeof(float), 256);
   L.total = off + 256;
   return L;
 }

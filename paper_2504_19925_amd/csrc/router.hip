@@ -6,7 +6,7 @@
 // step 32.  Operands pass through registers into LDS (rows padded to 80 bytes) so that either
 // side may be reduction-contiguous (16-byte loads) or reduction-strided (8 coalesced
 // scalar loads), bf16 or fp32 in memory; many workgroups per compute unit hide the latency.
-// The weight gradient's reduction runs over all T tokens: it is cut into chunks of 2048
+// The weight gradient's reduction runs over all T tokens: it is cut into chunks of 512
 // tokens whose partial products are summed by a second kernel in a fixed order.
 // fp32 configurations take a plain FMA kernel (one output per thread) instead.
 #include "common.h"
@@ -19,7 +19,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float rfloatx16;
 constexpr int RT = 128;        // tile rows and columns
 constexpr int RK = 32;         // reduction step
 constexpr int RLD = RK + 8;    // padded LDS row (elements)
-constexpr int RCHUNK = 2048;   // tokens per partial weight gradient
+constexpr int RCHUNK = 512;    // tokens per partial weight gradient
 
 enum { R_FWD = 0, R_DX = 1, R_DW = 2 };
 
@@ -49,6 +49,11 @@ __device__ __forceinline__ uint4 load8(const void* src, long long ld, int r, int
   if (CONTIG && !F32 && k + 8 <= kend) {
     return *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src) + (long long)r * ld + k);
   }
+  if (CONTIG && F32 && k + 8 <= kend && (ld & 3) == 0) {
+    const float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + (long long)r * ld + k);
+    const float4 c = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + (long long)r * ld + k + 4);
+    return make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(c.x, c.y), pack_bf16x2(c.z, c.w));
+  }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const long long at = CONTIG ? (long long)r * ld + k + i : (long long)(k + i) * ld + r;
@@ -58,6 +63,45 @@ __device__ __forceinline__ uint4 load8(const void* src, long long ld, int r, int
       v[i] = 0.f;
   }
   return pack8(v);
+}
+
+// Fill of a reduction-strided operand (memory [k][r], r contiguous): thread -> (k-row, 8
+// consecutive r), one vector load (16 bytes bf16 / 32 bytes fp32), then the 8 values are
+// scattered into the [r][k] LDS tile.  512 pieces per 32-deep step, two per thread.
+template <bool F32>
+__device__ __forceinline__ void fill_strided(uint16_t* tile, const void* src, long long ld, int r0,
+                                             int rows, int k0, int kend, int tid) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int u = tid + 256 * h;
+    const int kl = u >> 4, r8 = (u & 15) * 8;
+    const int k = k0 + kl, r = r0 + r8;
+    uint16_t v[8];
+    if (k < kend && r + 7 < rows) {
+      if (F32) {
+        const float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + (long long)k * ld + r);
+        const float4 b = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + (long long)k * ld + r + 4);
+        const float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = f32_to_bf16(f[i]);
+      } else {
+        const uint4 q = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src) + (long long)k * ld + r);
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { v[2 * i] = (uint16_t)(w[i] & 0xffffu); v[2 * i + 1] = (uint16_t)(w[i] >> 16); }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        v[i] = 0;
+        if (k < kend && r + i < rows)
+          v[i] = F32 ? f32_to_bf16(static_cast<const float*>(src)[(long long)k * ld + r + i])
+                     : static_cast<const uint16_t*>(src)[(long long)k * ld + r + i];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) tile[(r8 + i) * RLD + kl] = v[i];
+  }
 }
 
 template <int MODE>
@@ -84,29 +128,28 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   for (int k0 = kbeg; k0 < kend; k0 += RK) {
-    // fill: 128 rows x 4 pieces of 8 per operand, two per thread.  Reduction-contiguous
-    // operands walk a row with consecutive threads, strided ones walk the rows.
+    // fill: per operand 128 rows x 32 reduction indices.  Reduction-contiguous operands:
+    // thread -> (row, 8 consecutive k), 16-byte LDS store; strided ones: see fill_strided.
+    if (MODE == R_DW) {
+      fill_strided<true>(As, p.dl, p.E, m0, M, k0, kend, tid);
+    } else {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int u = tid + 256 * h;
-      {
-        constexpr bool contig = MODE != R_DW;
-        const int r = contig ? u >> 2 : u & 127, piece = contig ? u & 3 : u >> 7;
-        uint4 v;
-        if (MODE == R_FWD) v = load8<true, false>(p.X, p.d, m0 + r, M, k0 + 8 * piece, kend);
-        else if (MODE == R_DX) v = load8<true, true>(p.dl, p.E, m0 + r, M, k0 + 8 * piece, kend);
-        else v = load8<false, true>(p.dl, p.E, m0 + r, M, k0 + 8 * piece, kend);
+      for (int h = 0; h < 2; ++h) {
+        const int u = tid + 256 * h, r = u >> 2, piece = u & 3;
+        const uint4 v = MODE == R_FWD ? load8<true, false>(p.X, p.d, m0 + r, M, k0 + 8 * piece, kend)
+                                      : load8<true, true>(p.dl, p.E, m0 + r, M, k0 + 8 * piece, kend);
         *reinterpret_cast<uint4*>(&As[r * RLD + 8 * piece]) = v;
       }
-      {
-        constexpr bool contig = MODE == R_FWD;
-        const int r = contig ? u >> 2 : u & 127, piece = contig ? u & 3 : u >> 7;
-        uint4 v;
-        if (MODE == R_FWD) v = load8<true, false>(p.Wr, p.d, n0 + r, N, k0 + 8 * piece, kend);
-        else if (MODE == R_DX) v = load8<false, false>(p.Wr, p.d, n0 + r, N, k0 + 8 * piece, kend);
-        else v = load8<false, false>(p.X, p.d, n0 + r, N, k0 + 8 * piece, kend);
-        *reinterpret_cast<uint4*>(&Bs[r * RLD + 8 * piece]) = v;
+    }
+    if (MODE == R_FWD) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int u = tid + 256 * h, r = u >> 2, piece = u & 3;
+        *reinterpret_cast<uint4*>(&Bs[r * RLD + 8 * piece]) =
+            load8<true, false>(p.Wr, p.d, n0 + r, N, k0 + 8 * piece, kend);
       }
+    } else {
+      fill_strided<false>(Bs, MODE == R_DX ? p.Wr : p.X, p.d, n0, N, k0, kend, tid);
     }
     __syncthreads();
 #pragma unroll
@@ -183,20 +226,24 @@ __global__ __launch_bounds__(256) void router_reduce_kernel(const float* __restr
   }
 }
 
-// db[e] = sum_t dl[t,e]: one workgroup per class, fixed summation tree
-__global__ __launch_bounds__(256) void router_bias_grad_kernel(const float* __restrict__ dl, int T, int E,
-                                                               float* __restrict__ db) {
-  __shared__ float red[256];
-  const int e = blockIdx.x;
-  float s = 0.f;
-  for (int t = threadIdx.x; t < T; t += 256) s += dl[(long long)t * E + e];
-  red[threadIdx.x] = s;
-  __syncthreads();
-  for (int o = 128; o >= 1; o >>= 1) {
-    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
-    __syncthreads();
+// db[e] = sum_t dl[t,e] in two fixed-order stages: per chunk of 256 tokens (threads along
+// e, so every row is read contiguously), then over the chunks
+__global__ __launch_bounds__(256) void router_bias_partial_kernel(const float* __restrict__ dl, int T, int E,
+                                                                  float* __restrict__ part) {
+  const int t0 = blockIdx.x * 256, t1 = min(T, t0 + 256);
+  for (int e = threadIdx.x; e < E; e += 256) {
+    double s = 0.0;   // the summands cancel heavily: accumulate in binary64
+    for (int t = t0; t < t1; ++t) s += (double)dl[(long long)t * E + e];
+    part[(long long)blockIdx.x * E + e] = (float)s;
   }
-  if (threadIdx.x == 0) db[e] = red[0];
+}
+__global__ __launch_bounds__(256) void router_bias_final_kernel(const float* __restrict__ part, int nchunk,
+                                                                int E, float* __restrict__ db) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= E) return;
+  double s = 0.0;
+  for (int c = 0; c < nchunk; ++c) s += (double)part[(long long)c * E + e];
+  db[e] = (float)s;
 }
 
 // ---- fp32 configurations: one output element per thread, plain FMAs in index order
@@ -288,7 +335,13 @@ extern "C" int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* W
     SYMI_TIMED(K_ROUTER_DW, st, (router_dw_f32_kernel<<<cdiv((long long)E * d, 256), 256, 0, st>>>(
         dlogits, static_cast<const float*>(X), dWr, T, E, d)));
   }
-  if (db) SYMI_TIMED(K_ROUTER_DW, st, (router_bias_grad_kernel<<<E, 256, 0, st>>>(dlogits, T, E, db)));
+  if (db) {
+    float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + L.router_bias_partial);
+    const int nb = cdiv(T, 256);
+    if (nb > 0)
+      SYMI_TIMED(K_ROUTER_DW, st, (router_bias_partial_kernel<<<nb, 256, 0, st>>>(dlogits, T, E, part)));
+    SYMI_TIMED(K_ROUTER_DW, st, (router_bias_final_kernel<<<cdiv(E, 256), 256, 0, st>>>(part, nb, E, db)));
+  }
   SYMI_LAUNCH_CHECK("symi_router_bwd");
   return SYMI_OK;
 }
