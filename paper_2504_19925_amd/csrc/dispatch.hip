@@ -167,19 +167,22 @@ __global__ __launch_bounds__(DT) void chunk_rank_kernel(const int32_t* __restric
   }
 }
 
-// dst[row] = src[map[row] / div] for rows of `vec_per_row` 16-byte pieces.
-__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ src,
-                                                          uint4* __restrict__ dst,
-                                                          const int32_t* __restrict__ map, int div,
-                                                          long long n_vec, int vec_per_row,
-                                                          const int32_t* __restrict__ n_rows) {
-  if (n_rows) n_vec = (long long)*n_rows * vec_per_row;   // only the kept rows exist
+// Xp[row_of_assign[t*k + j]] = X[t] for every choice j of token t, rows of `vec_per_row`
+// 16-byte pieces.  Walking the tokens (not the rows) reads every token once, whatever k is;
+// the k destination rows are whole contiguous rows.  Dropped assignments (row -1) are skipped.
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4* __restrict__ src,
+                                                           uint4* __restrict__ dst,
+                                                           const int32_t* __restrict__ roa, int k,
+                                                           long long n_vec, int vec_per_row) {
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n_vec;
        i += (long long)gridDim.x * 256) {
-    const long long row = i / vec_per_row;
-    const int c = (int)(i - row * vec_per_row);
-    const long long s = map[row] / div;
-    dst[i] = src[s * vec_per_row + c];
+    const long long t = i / vec_per_row;
+    const int c = (int)(i - t * vec_per_row);
+    const uint4 x = src[i];
+    for (int j = 0; j < k; ++j) {
+      const long long row = roa[t * k + j];
+      if (row >= 0) dst[row * vec_per_row + c] = x;
+    }
   }
 }
 
@@ -313,10 +316,9 @@ static int dispatch_impl(const char* who, const symi_cfg* cfg, int slot_cap, con
         idx, A, E, blk, row_of_assign, assign_of_row, tab)));
     const int w = cfg->dtype == SYMI_BF16 ? 2 : 4;
     const int vpr = cfg->d * w / 16;
-    const long long nvec = (long long)A * vpr;
-    SYMI_TIMED(K_GATHER, st, (gather_rows_kernel<<<grid_for(nvec, 256 * 4), 256, 0, st>>>(
-        static_cast<const uint4*>(X), static_cast<uint4*>(Xp), assign_of_row, cfg->k, nvec, vpr,
-        slot_cap > 0 ? slot_offsets + cfg->S_tot : nullptr)));
+    const long long nvec = (long long)cfg->T * vpr;
+    SYMI_TIMED(K_GATHER, st, (scatter_rows_kernel<<<grid_for(nvec, 256 * 2), 256, 0, st>>>(
+        static_cast<const uint4*>(X), static_cast<uint4*>(Xp), row_of_assign, cfg->k, nvec, vpr)));
   }
   SYMI_LAUNCH_CHECK(who);
   return SYMI_OK;
