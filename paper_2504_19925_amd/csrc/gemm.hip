@@ -433,93 +433,103 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   __builtin_amdgcn_s_waitcnt(0xC07F);
   wait_vmcnt0();
 
-  // ---- epilogue.  After the MFMA a lane owns one output row (lane%32) and, per 8-column
-  // group g, the 4 columns 8g + 4*(lane/32) ..; the two half-waves hold the two halves of
-  // every group.  One v_permlane32_swap per register lets the lower half-wave collect all
-  // 8 columns of the even groups and the upper half-wave those of the odd groups, so every
-  // store is 16 bytes (bf16) or 32 bytes (fp32) of one row.
-  const int hw = lane >> 5;
-  auto swap2 = [&](unsigned& a, unsigned& b) {   // a: even group, b: odd group (see above)
-    const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
-    a = r[0];
-    b = r[1];
-  };
+  // ---- epilogue.  After the MFMA a lane owns one output row (lane%32) of each 32-row
+  // block and, per 8-column group g, the 4 columns 8g + 4*(lane/32) ..: stored like that, a
+  // wavefront store would touch 64 cache lines with 16 bytes each, and the store path is
+  // paid per line touched.  The operand stages are free now, so every wavefront turns its
+  // 32-row blocks around through a private piece of LDS (written in the MFMA layout, read
+  // back row by row, 16 bytes per lane) and each store instruction writes whole lines:
+  // 4 rows x 256 B (bf16 outputs), 8 rows x 128 B (u, v, h) or 2 rows x 512 B (fp32).
+  __syncthreads();   // every wavefront's dummy loads have landed, nobody reads operands any more
+  const int hw = lane >> 5, r32 = lane & 31;
+  uint16_t* const stg = smem + wave * (16 * 1024);   // 32 KB per wavefront
+  constexpr int LDB = 136;   // bf16 row of 128 columns + pad (272 B, a multiple of 16)
+  constexpr int LDH = 72;    // u / v / h rows of 64 hidden units + pad (144 B)
+  constexpr int LDF = 132;   // fp32 row of 128 columns + pad (528 B)
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int row = row0 + wm * 128 + i * 32 + (lane & 31);
-    if (row < row1) {
-      if (MODE == FWD1) {
-        uint16_t* UVo = static_cast<uint16_t*>(p.UVout);
-        uint16_t* Ho = static_cast<uint16_t*>(p.H);
+    const int rbase = row0 + wm * 128 + i * 32;   // first output row of this block
+    if (MODE == FWD1) {
+      uint16_t* const su = stg;
+      uint16_t* const sv = stg + 32 * LDH;
+      uint16_t* const sh = stg + 64 * LDH;
 #pragma unroll
-        for (int hb = 0; hb < 2; ++hb)
+      for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
-          for (int ge = 0; ge < 4; ge += 2) {
-            unsigned pu[2][2], pv[2][2], ph[2][2];   // [even/odd group][column pair]
+        for (int g = 0; g < 4; ++g) {
+          unsigned pu[2], pv[2], ph[2];
 #pragma unroll
-            for (int o = 0; o < 2; ++o)
-#pragma unroll
-              for (int c2 = 0; c2 < 2; ++c2) {
-                const int r = (ge + o) * 4 + 2 * c2;
-                const float u0 = acc[i][2 * hb][r], u1 = acc[i][2 * hb][r + 1];
-                const float v0 = acc[i][2 * hb + 1][r], v1 = acc[i][2 * hb + 1][r + 1];
-                pu[o][c2] = pack_bf16x2(u0, u1);
-                pv[o][c2] = pack_bf16x2(v0, v1);
-                ph[o][c2] = pack_bf16x2(u0 * sigmoid_fast(u0) * v0, u1 * sigmoid_fast(u1) * v1);
-              }
-#pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2) {
-              swap2(pu[0][c2], pu[1][c2]);
-              swap2(pv[0][c2], pv[1][c2]);
-              swap2(ph[0][c2], ph[1][c2]);
-            }
-            const int hu = n0 + wn * 64 + hb * 32 + (ge + hw) * 8;
-            if (hu < p.f) {
-              const long long o = (long long)row * 2 * p.f + hu;
-              *reinterpret_cast<uint4*>(UVo + o) = make_uint4(pu[0][0], pu[0][1], pu[1][0], pu[1][1]);
-              *reinterpret_cast<uint4*>(UVo + o + p.f) = make_uint4(pv[0][0], pv[0][1], pv[1][0], pv[1][1]);
-              *reinterpret_cast<uint4*>(Ho + (long long)row * p.f + hu) =
-                  make_uint4(ph[0][0], ph[0][1], ph[1][0], ph[1][1]);
-            }
+          for (int c2 = 0; c2 < 2; ++c2) {
+            const int r = g * 4 + 2 * c2;
+            const float u0 = acc[i][2 * hb][r], u1 = acc[i][2 * hb][r + 1];
+            const float v0 = acc[i][2 * hb + 1][r], v1 = acc[i][2 * hb + 1][r + 1];
+            pu[c2] = pack_bf16x2(u0, u1);
+            pv[c2] = pack_bf16x2(v0, v1);
+            ph[c2] = pack_bf16x2(u0 * sigmoid_fast(u0) * v0, u1 * sigmoid_fast(u1) * v1);
           }
-      } else {
+          const int at = r32 * LDH + hb * 32 + 8 * g + 4 * hw;
+          *reinterpret_cast<uint2*>(su + at) = make_uint2(pu[0], pu[1]);
+          *reinterpret_cast<uint2*>(sv + at) = make_uint2(pv[0], pv[1]);
+          *reinterpret_cast<uint2*>(sh + at) = make_uint2(ph[0], ph[1]);
+        }
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      uint16_t* UVo = static_cast<uint16_t*>(p.UVout);
+      uint16_t* Ho = static_cast<uint16_t*>(p.H);
+      const int hu = n0 + wn * 64 + (lane & 7) * 8;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+      for (int it = 0; it < 4; ++it) {
+        const int rr = it * 8 + (lane >> 3);
+        const int row = rbase + rr;
+        const uint4 xu = *reinterpret_cast<const uint4*>(su + rr * LDH + (lane & 7) * 8);
+        const uint4 xv = *reinterpret_cast<const uint4*>(sv + rr * LDH + (lane & 7) * 8);
+        const uint4 xh = *reinterpret_cast<const uint4*>(sh + rr * LDH + (lane & 7) * 8);
+        if (row < row1 && hu < p.f) {
+          const long long o = (long long)row * 2 * p.f + hu;
+          *reinterpret_cast<uint4*>(UVo + o) = xu;
+          *reinterpret_cast<uint4*>(UVo + o + p.f) = xv;
+          *reinterpret_cast<uint4*>(Ho + (long long)row * p.f + hu) = xh;
+        }
+      }
+    } else if (MODE == FWD2 || MODE == BWD_DX || MODE == BWD_DH) {
 #pragma unroll
-          for (int ge = 0; ge < 4; ge += 2) {
-            const int col = n0 + wn * 128 + j * 32 + (ge + hw) * 8;
-            if (MODE == FWD2 || MODE == BWD_DX || MODE == BWD_DH) {
-              unsigned px[2][2];
+      for (int j = 0; j < 4; ++j)
 #pragma unroll
-              for (int o = 0; o < 2; ++o)
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<uint2*>(stg + r32 * LDB + 32 * j + 8 * g + 4 * hw) =
+              make_uint2(pack_bf16x2(acc[i][j][4 * g], acc[i][j][4 * g + 1]),
+                         pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]));
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      uint16_t* Co = static_cast<uint16_t*>(p.C);
+      const int col = n0 + wn * 128 + (lane & 15) * 8;
 #pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2)
-                  px[o][c2] = pack_bf16x2(acc[i][j][(ge + o) * 4 + 2 * c2], acc[i][j][(ge + o) * 4 + 2 * c2 + 1]);
-              swap2(px[0][0], px[1][0]);
-              swap2(px[0][1], px[1][1]);
-              if (col < p.N) {
-                uint16_t* Co = static_cast<uint16_t*>(p.C);
-                *reinterpret_cast<uint4*>(Co + (long long)row * p.N + col) =
-                    make_uint4(px[0][0], px[0][1], px[1][0], px[1][1]);
-              }
-            } else {  // weight gradients, fp32
-              unsigned xe[4], xo[4];
+      for (int it = 0; it < 8; ++it) {
+        const int rr = it * 4 + (lane >> 4);
+        const int row = rbase + rr;
+        const uint4 x = *reinterpret_cast<const uint4*>(stg + rr * LDB + (lane & 15) * 8);
+        if (row < row1 && col < p.N) *reinterpret_cast<uint4*>(Co + (long long)row * p.N + col) = x;
+      }
+    } else {   // weight gradients, fp32
+      float* const sf = reinterpret_cast<float*>(stg);
 #pragma unroll
-              for (int c = 0; c < 4; ++c) {
-                xe[c] = __float_as_uint(acc[i][j][ge * 4 + c]);
-                xo[c] = __float_as_uint(acc[i][j][(ge + 1) * 4 + c]);
-                swap2(xe[c], xo[c]);
-              }
-              if (col < p.N) {
-                float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride + (long long)row * p.N + col;
-                *reinterpret_cast<uint4*>(Co) = make_uint4(xe[0], xe[1], xe[2], xe[3]);
-                *reinterpret_cast<uint4*>(Co + 4) = make_uint4(xo[0], xo[1], xo[2], xo[3]);
-              }
-            }
-          }
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(sf + r32 * LDF + 32 * j + 8 * g + 4 * hw) =
+              make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride;
+      const int col = n0 + wn * 128 + (lane & 31) * 4;
+#pragma unroll
+      for (int it = 0; it < 16; ++it) {
+        const int rr = it * 2 + (lane >> 5);
+        const int row = rbase + rr;
+        const float4 x = *reinterpret_cast<const float4*>(sf + rr * LDF + (lane & 31) * 4);
+        if (row < row1 && col < p.N) *reinterpret_cast<float4*>(Co + (long long)row * p.N + col) = x;
       }
     }
-    __builtin_amdgcn_sched_barrier(0);   // one 32-row block at a time: bounds the registers in flight
+    // the next block reuses the staging area: its writes must not pass these reads
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
