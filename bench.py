@@ -140,29 +140,39 @@ def run_gpu(args):
         st.first_slot, st.first_slot_next = st.first_slot_next, st.first_slot
         st.placement, st.placement_next = st.placement_next, st.placement
 
-    fwd_bwd_ms = None
+    def timed(n_steps, first):
+        """n_steps steps with a HIP event pair around every launch; returns ms per step and
+        {kernel: (average ms per launch, launches)}."""
+        Hn.sync()
+        symi.symi_timing_reset()
+        symi.symi_timing_enable(True)
+        Hn.sync()
+        t0 = time.perf_counter()
+        for i in range(n_steps):
+            step(first + i)
+        Hn.sync()
+        t1 = time.perf_counter()
+        symi.symi_timing_enable(False)
+        got = {}
+        for kid in range(symi.symi_kernel_count()):
+            ms, n = symi.symi_timing_read(kid)
+            if n:
+                got[symi.symi_kernel_name(kid)] = (ms / n, n)
+        symi.symi_timing_reset()
+        return (t1 - t0) * 1e3 / n_steps, got
+
+    symi.symi_set_overlap(not args.no_overlap)
     for i in range(args.warmup):
         step(i)
-    Hn.sync()
-    symi.symi_timing_reset()
-    symi.symi_timing_enable(True)
-    Hn.sync()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    Hn.sync()
-    t1 = time.perf_counter()
-    symi.symi_timing_enable(False)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    # per-kernel durations of the timed region
+    # the timed region: the library as it ships (the backward's two chains of products may
+    # share the chip on two streams, so kernel durations overlap there)
+    ms_per_step, times_region = timed(args.steps, args.warmup)
+    # per-kernel durations and the roofline come from the same steps run again with one kernel
+    # at a time on the stream, which is also what the committed rocprofv3 summary shows
+    symi.symi_set_overlap(False)
+    ms_serial, times = timed(args.steps, args.warmup)
+    symi.symi_set_overlap(not args.no_overlap)
     w = 2 if c.dtype == "bf16" else 4
-    times = {}
-    for kid in range(symi.symi_kernel_count()):
-        ms, n = symi.symi_timing_read(kid)
-        if n:
-            times[symi.symi_kernel_name(kid)] = (ms / n, n)
-    symi.symi_timing_reset()
 
     # slots that actually hold rows (their weights are the ones a step must read)
     nonempty = []
@@ -216,6 +226,8 @@ def run_gpu(args):
         "roofline": roof,
         "fwd_bwd_tokens_per_s": round(c.T / (fwd_bwd_ms * 1e-3), 1),
         "gpu_kernel_ms_per_step": round(gpu_ms, 4),
+        "ms_per_step_one_kernel_at_a_time": round(ms_serial, 4),
+        "kernel_table": "measured in a second pass of the same steps with symi_set_overlap(0)",
         "nonempty_slots_mean": round(mean_nonempty, 2),
         "kernels": kernels,
     }
@@ -277,6 +289,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="keep every kernel on one stream also in the timed region (symi_set_overlap(0))")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device copy (reference for the HBM traffic counters)")
     ap.add_argument("--survival", type=float, default=None, metavar="CAPACITY_FACTOR",

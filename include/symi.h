@@ -185,6 +185,13 @@ int symi_router_fwd(const symi_cfg* cfg, const void* X, const void* Wr, const fl
 int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* Wr, const float* dlogits,
                     float* dWr, float* db, void* dX, void* ws, void* stream);
 
+/* symi_expert_bwd / symi_expert_bwd_slots enqueue the weight-gradient products on a helper
+ * stream of the library (one per device, created at the first call) that is forked from and
+ * joined back into `stream` with events: for the caller everything is still ordered on
+ * `stream`.  It does so when the products are only a few rounds of workgroups (small
+ * batches); symi_set_overlap(0) keeps every kernel on `stream` itself, (1) is the default. */
+int symi_set_overlap(int on);
+
 /* The replica gradient path as the paper draws it (Sec. 4.1, Fig. 7), as an alternative to
  * symi_expert_bwd's fused per-class sum.  symi_expert_bwd_slots is symi_expert_bwd with one
  * weight gradient per replica SLOT, summed over that slot's own rows only:

@@ -761,6 +761,51 @@ extern "C" int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_
   return SYMI_OK;
 }
 
+// compute units of the current device
+static int device_cus() {
+  static int cus[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    cus[dev] = n;
+  }
+  return cus[dev];
+}
+
+// The backward's five products form two chains that only meet at du|dv:
+//   dh -> du|dv -> dXp          and          dW2 (needs dYp, H only) -> dW1 (needs du|dv)
+// Run back to back each launch rounds its tile count up to whole rounds of 256 workgroups
+// (config c2: 296 tiles of the dXp product are two rounds, the second one 84 % empty) and
+// the store-bound zero tiles of the weight gradients never meet the MFMA-bound tiles.  The
+// second chain is therefore enqueued on a helper stream (one per device, created at the
+// first call, default priority, non-blocking) forked from and joined back into the caller's
+// stream with events, so workgroups of both chains share the chip.  This is done when the
+// dXp product has fewer than 8 rounds of tiles; symi_set_overlap(0) turns it off altogether
+// (everything on the caller's stream, in order).
+struct SideStream {
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, mid = nullptr, join = nullptr;
+  bool ok = false, tried = false;
+};
+static bool g_overlap = true;
+static SideStream* side_stream() {
+  static SideStream side[64];
+  int dev = 0;
+  if (!g_overlap || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  SideStream& x = side[dev];
+  if (!x.tried) {
+    x.tried = true;
+    x.ok = hipStreamCreateWithFlags(&x.s, hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&x.fork, hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&x.mid, hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&x.join, hipEventDisableTiming) == hipSuccess;
+    if (!x.ok) (void)hipGetLastError();
+  }
+  return x.ok ? &x : nullptr;
+}
+
 // per_slot = false: dW1_out / dW2_out are per class (all replica slots summed in the GEMM);
 // per_slot = true: one gradient per replica slot (its own rows only)
 static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp, const void* Xp,
@@ -788,6 +833,22 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
   p.d = cfg->d;
   p.f = cfg->f;
   SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, first_slot, cfg->S_tot, cfg->E, map, order)));
+  // worth it only while a product is a few rounds of workgroups: with many rounds the chip is
+  // full anyway and two kernels sharing it only disturb each other's L2 locality
+  const bool few_rounds = (long long)max_mtiles * cdiv(cfg->d, BN) < 8LL * device_cus();
+  SideStream* side = A > 0 && few_rounds ? side_stream() : nullptr;
+  hipStream_t sw = st;   // stream of the weight-gradient chain
+  if (side) {
+    bool ok = hipEventRecord(side->fork, st) == hipSuccess &&
+              hipStreamWaitEvent(side->s, side->fork, 0) == hipSuccess;
+    if (ok) sw = side->s; else { side = nullptr; (void)hipGetLastError(); }
+  }
+  // class gradients, first half (classes without rows get zeros: their reduction is empty)
+  GemmParams pw = p;
+  pw.A = dYp; pw.B = H; pw.C = dW2_class;
+  pw.c_group_stride = (long long)cfg->d * cfg->f;
+  pw.M = cfg->d; pw.N = cfg->f;
+  launch_gemm<WGRAD2>(cfg, pw, cfg->f, 0, sw);
   if (A > 0) {
     // dh = dYp W2, then du, dv
     const bool bf16 = cfg->dtype == SYMI_BF16;
@@ -803,22 +864,34 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
       SYMI_TIMED(K_DSWIGLU, st, (dswiglu_bf16_kernel<<<(unsigned)g, 256, 0, st>>>(
           static_cast<const uint4*>(dHbuf), static_cast<const uint4*>(UV), static_cast<uint4*>(dUV), A, cfg->f / 8)));
     }
+    if (side) {   // du|dv is complete: the other chain may go on to dW1
+      if (hipEventRecord(side->mid, st) != hipSuccess || hipStreamWaitEvent(side->s, side->mid, 0) != hipSuccess) {
+        set_error("%s: event hand-over between the two streams failed", who);
+        return SYMI_EHIP;
+      }
+    }
     // dXp = dUV W1
     p.A = dUV; p.B = W1_slots; p.C = dXp;
     p.b_group_stride = 2LL * cfg->f * cfg->d;
     p.N = cfg->d; p.K = 2 * cfg->f;
     launch_gemm<BWD_DX>(cfg, p, cfg->d, max_mtiles, st);
   }
-  // class gradients (classes without rows get zeros: their reduction is empty)
-  p.A = dYp; p.B = H; p.C = dW2_class;
-  p.c_group_stride = (long long)cfg->d * cfg->f;
-  p.M = cfg->d; p.N = cfg->f;
-  launch_gemm<WGRAD2>(cfg, p, cfg->f, 0, st);
-  p.A = dUV; p.B = Xp; p.C = dW1_class;
-  p.c_group_stride = 2LL * cfg->f * cfg->d;
-  p.M = 2 * cfg->f; p.N = cfg->d;
-  launch_gemm<WGRAD1>(cfg, p, cfg->d, 0, st);
+  pw.A = dUV; pw.B = Xp; pw.C = dW1_class;
+  pw.c_group_stride = 2LL * cfg->f * cfg->d;
+  pw.M = 2 * cfg->f; pw.N = cfg->d;
+  launch_gemm<WGRAD1>(cfg, pw, cfg->d, 0, sw);
+  if (side) {
+    if (hipEventRecord(side->join, side->s) != hipSuccess || hipStreamWaitEvent(st, side->join, 0) != hipSuccess) {
+      set_error("%s: joining the helper stream failed", who);
+      return SYMI_EHIP;
+    }
+  }
   SYMI_LAUNCH_CHECK(who);
+  return SYMI_OK;
+}
+
+extern "C" int symi_set_overlap(int on) {
+  g_overlap = on != 0;
   return SYMI_OK;
 }
 

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2504_19925_amd as symi
 import workloads as wl
 from oracle import symi_oracle as O
 from tests import harness as Hn
@@ -214,3 +215,35 @@ def test_place_device_matches_oracle_on_random_popularities():
         assert counts.cpu().tolist() == oc.tolist(), (pop[:16], S)
         assert placement.cpu().tolist() == op.tolist()
         assert first.cpu().tolist() == of.tolist()
+
+
+def test_backward_on_two_streams_equals_backward_on_one():
+    """symi_expert_bwd may run its two chains of products on two streams (small batches); the
+    results are the same bits as with every kernel on the caller's stream, also when the
+    caller's stream is not the default one."""
+    c = _small("c2")
+    st = Hn.State(c)
+    X, logits, dY = Hn.draw_inputs(c, 0)
+    st.place_current()
+    st.forward(X, logits)
+    outs = []
+    try:
+        for overlap, own_stream in ((True, False), (False, False), (True, True)):
+            symi.symi_set_overlap(overlap)
+            for t in (st.dX, st.dW1, st.dW2, st.dXp):
+                t.fill_(float("nan"))
+            if own_stream:
+                s = torch.cuda.Stream()
+                s.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(s):
+                    st.backward(dY, logits)
+                torch.cuda.current_stream().wait_stream(s)
+            else:
+                st.backward(dY, logits)
+            Hn.sync()
+            outs.append([t.clone() for t in (st.dX, st.dW1, st.dW2, st.dgate, st.dlogits)])
+    finally:
+        symi.symi_set_overlap(True)
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
