@@ -44,8 +44,7 @@ def kernel_work(c, w, nonempty_slots):
         "gather_rows": (0, T * d * w + A * d * w + 4 * A),
         "gemm_fwd1": (2 * A * d * 2 * f, Sn * 2 * f * d * w + A * d * w + A * 3 * f * w),
         "gemm_fwd2": (2 * A * f * d, Sn * d * f * w + A * f * w + A * d * w),
-        "gemm_bwd_dh": (2 * A * d * f, Sn * d * f * w + A * d * w + A * f * w),
-        "dswiglu": (0, A * f * w * 5),
+        "gemm_bwd_dh": (2 * A * d * f, Sn * d * f * w + A * d * w + 4 * A * f * w),
         "gemm_bwd_dx": (2 * A * 2 * f * d, Sn * 2 * f * d * w + A * 2 * f * w + A * d * w),
         "gemm_wgrad2": (2 * A * d * f, A * d * w + A * f * w + E * d * f * 4),
         "gemm_wgrad1": (2 * A * 2 * f * d, A * 2 * f * w + A * d * w + E * 2 * f * d * 4),

@@ -64,8 +64,6 @@ WsLayout ws_layout(const symi_cfg* c) {
   off += align_up((size_t)c->E * sizeof(int32_t), 256);
   L.duv = off;
   off += align_up(A * 2 * c->f * w, 256);
-  L.dh = off;
-  off += align_up(A * c->f * w, 256);
   L.router_partial = off;
   off += align_up(((size_t)c->T + 511) / 512 * c->E * c->d * sizeof(float), 256);
   L.router_bias_partial = off;

@@ -76,7 +76,6 @@ struct WsLayout {
   size_t tile_map;     // expert fwd/bwd: m-tile table, see gemm.hip
   size_t class_order;  // expert bwd: classes by decreasing row count
   size_t duv;          // expert bwd: dUV [A,2f] in the activation dtype
-  size_t dh;           // expert bwd (bf16): dh [A,f]
   size_t router_partial;  // router bwd (bf16): partial weight gradients [chunks,E,d] f32
   size_t router_bias_partial;  // router bwd: partial bias gradients [chunks,E] f32
   size_t total;

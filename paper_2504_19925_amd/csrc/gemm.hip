@@ -7,7 +7,7 @@
 // MFMA 32x32x16 bf16 instruction; a plain-FMA twin serves fp32 configurations):
 //   FWD1   [u|v] = Xp  * W1^T      + SwiGLU epilogue writing u, v and h = silu(u)*v
 //   FWD2   Yp    = H   * W2^T
-//   BWD_DH dh    = dYp * W2        then du, dv from dh, u, v (streaming kernel; fused epilogue in fp32)
+//   BWD_DH dh    = dYp * W2        turned into du, dv from the saved u, v in the epilogue
 //   BWD_DX dXp   = dUV * W1
 //   WGRAD2 dW2_e = dYp^T * H       over all rows of class e
 //   WGRAD1 dW1_e = dUV^T * Xp      over all rows of class e
@@ -446,6 +446,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   constexpr int LDB = 136;   // bf16 row of 128 columns + pad (272 B, a multiple of 16)
   constexpr int LDH = 72;    // u / v / h rows of 64 hidden units + pad (144 B)
   constexpr int LDF = 132;   // fp32 row of 128 columns + pad (528 B)
+  uint4 uvu[2][8], uvv[2][8];   // BWD_DH: saved u, v of the current and the next 32-row block
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int rbase = row0 + wm * 128 + i * 32;   // first output row of this block
@@ -490,7 +491,67 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
           *reinterpret_cast<uint4*>(Ho + (long long)row * p.f + hu) = xh;
         }
       }
-    } else if (MODE == FWD2 || MODE == BWD_DX || MODE == BWD_DH) {
+    } else if (MODE == BWD_DH) {
+      // dh stays in fp32: staged like a weight-gradient block, then every lane takes 8
+      // consecutive hidden units of one row, combines them with the saved u and v (16 bytes
+      // each, whole lines per instruction) and writes du = dh v s (1 + u (1 - s)),
+      // dv = dh u s, s = sigmoid(u).  The u, v loads of block i + 1 are issued before block i
+      // is worked on, so their latency hides behind it.
+      float* const sf = reinterpret_cast<float*>(stg);
+      const uint16_t* UVi = static_cast<const uint16_t*>(p.UV);
+      uint16_t* Co = static_cast<uint16_t*>(p.C);
+      const int col = n0 + wn * 128 + (lane & 15) * 8;
+      auto load_uv = [&](int blk, uint4 (&uu)[8], uint4 (&vv)[8]) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+          const int row = row0 + wm * 128 + blk * 32 + it * 4 + (lane >> 4);
+          if (row < row1 && col < p.N) {
+            const long long o = (long long)row * 2 * p.f + col;
+            uu[it] = *reinterpret_cast<const uint4*>(UVi + o);
+            vv[it] = *reinterpret_cast<const uint4*>(UVi + o + p.f);
+          }
+        }
+      };
+      if (i == 0) load_uv(0, uvu[0], uvv[0]);
+      if (i + 1 < 4) load_uv(i + 1, uvu[(i + 1) & 1], uvv[(i + 1) & 1]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(sf + r32 * LDF + 32 * j + 8 * g + 4 * hw) =
+              make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int rr = it * 4 + (lane >> 4);
+        const int row = rbase + rr;
+        const float4 d0 = *reinterpret_cast<const float4*>(sf + rr * LDF + (lane & 15) * 8);
+        const float4 d1 = *reinterpret_cast<const float4*>(sf + rr * LDF + (lane & 15) * 8 + 4);
+        if (row < row1 && col < p.N) {
+          const long long o = (long long)row * 2 * p.f + col;
+          const uint4 uu = uvu[i & 1][it], vv = uvv[i & 1][it];
+          const float dh[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+          const uint32_t uw[4] = {uu.x, uu.y, uu.z, uu.w}, vw[4] = {vv.x, vv.y, vv.z, vv.w};
+          uint32_t du[4], dv[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float o_du[2], o_dv[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const float u_ = __uint_as_float(h ? (uw[q] & 0xffff0000u) : (uw[q] << 16));
+              const float v_ = __uint_as_float(h ? (vw[q] & 0xffff0000u) : (vw[q] << 16));
+              const float sg = sigmoid_fast(u_);
+              o_du[h] = dh[2 * q + h] * v_ * sg * (1.f + u_ * (1.f - sg));
+              o_dv[h] = dh[2 * q + h] * u_ * sg;
+            }
+            du[q] = pack_bf16x2(o_du[0], o_du[1]);
+            dv[q] = pack_bf16x2(o_dv[0], o_dv[1]);
+          }
+          *reinterpret_cast<uint4*>(Co + o) = make_uint4(du[0], du[1], du[2], du[3]);
+          *reinterpret_cast<uint4*>(Co + o + p.f) = make_uint4(dv[0], dv[1], dv[2], dv[3]);
+        }
+      }
+    } else if (MODE == FWD2 || MODE == BWD_DX) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -530,43 +591,6 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
     // the next block reuses the staging area: its writes must not pass these reads
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_sched_barrier(0);
-  }
-}
-
-// du, dv from dh and the saved u, v (bf16 path; the fp32 twin fuses this into its epilogue):
-// du = dh * v * s * (1 + u * (1 - s)), dv = dh * u * s, s = sigmoid(u).  Pure streaming,
-// 16-byte pieces: 6 B read and 4 B written per hidden activation.
-__global__ __launch_bounds__(256) void dswiglu_bf16_kernel(const uint4* __restrict__ dH,
-                                                           const uint4* __restrict__ UV,
-                                                           uint4* __restrict__ dUV, long long rows,
-                                                           int f8) {
-  const long long n = rows * f8;
-  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
-    const long long r = i / f8;
-    const int c = (int)(i - r * f8);
-    const uint4 dh = dH[i];
-    const uint4 uu = UV[r * 2 * f8 + c];
-    const uint4 vv = UV[r * 2 * f8 + f8 + c];
-    const uint32_t dw[4] = {dh.x, dh.y, dh.z, dh.w}, uw[4] = {uu.x, uu.y, uu.z, uu.w},
-                   vw[4] = {vv.x, vv.y, vv.z, vv.w};
-    uint32_t du[4], dv[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float o_du[2], o_dv[2];
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const float d_ = __uint_as_float(h ? (dw[q] & 0xffff0000u) : (dw[q] << 16));
-        const float u_ = __uint_as_float(h ? (uw[q] & 0xffff0000u) : (uw[q] << 16));
-        const float v_ = __uint_as_float(h ? (vw[q] & 0xffff0000u) : (vw[q] << 16));
-        const float sg = sigmoid_fast(u_);
-        o_du[h] = d_ * v_ * sg * (1.f + u_ * (1.f - sg));
-        o_dv[h] = d_ * u_ * sg;
-      }
-      du[q] = pack_bf16x2(o_du[0], o_du[1]);
-      dv[q] = pack_bf16x2(o_dv[0], o_dv[1]);
-    }
-    dUV[r * 2 * f8 + c] = make_uint4(du[0], du[1], du[2], du[3]);
-    dUV[r * 2 * f8 + f8 + c] = make_uint4(dv[0], dv[1], dv[2], dv[3]);
   }
 }
 
@@ -850,20 +874,11 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
   pw.M = cfg->d; pw.N = cfg->f;
   launch_gemm<WGRAD2>(cfg, pw, cfg->f, 0, sw);
   if (A > 0) {
-    // dh = dYp W2, then du, dv
-    const bool bf16 = cfg->dtype == SYMI_BF16;
-    void* dHbuf = static_cast<char*>(ws) + L.dh;
-    p.A = dYp; p.B = W2_slots; p.C = bf16 ? dHbuf : dUV; p.UV = UV;
+    // dh = dYp W2, turned into du, dv in the epilogue (dh itself never reaches memory)
+    p.A = dYp; p.B = W2_slots; p.C = dUV; p.UV = UV;
     p.b_group_stride = (long long)cfg->d * cfg->f;
     p.N = cfg->f; p.K = cfg->d;
     launch_gemm<BWD_DH>(cfg, p, cfg->f, max_mtiles, st);
-    if (bf16) {
-      const long long pieces = A * (cfg->f / 8);
-      long long g = (pieces + 255) / 256;
-      if (g > 16384) g = 16384;
-      SYMI_TIMED(K_DSWIGLU, st, (dswiglu_bf16_kernel<<<(unsigned)g, 256, 0, st>>>(
-          static_cast<const uint4*>(dHbuf), static_cast<const uint4*>(UV), static_cast<uint4*>(dUV), A, cfg->f / 8)));
-    }
     if (side) {   // du|dv is complete: the other chain may go on to dW1
       if (hipEventRecord(side->mid, st) != hipSuccess || hipStreamWaitEvent(side->s, side->mid, 0) != hipSuccess) {
         set_error("%s: event hand-over between the two streams failed", who);
