@@ -81,7 +81,7 @@ static const char* const g_names[K_COUNT] = {
     "fill_i32", "route", "route_bwd", "place", "chunk_count", "chunk_scan", "chunk_rank",
     "gather_rows", "tile_map", "gemm_fwd1", "gemm_fwd2", "gemm_bwd_dh", "gemm_bwd_dx",
     "gemm_wgrad2", "gemm_wgrad1", "combine", "combine_bwd", "dispatch_bwd", "adam_to_replicas",
-    "dswiglu", "replica_allreduce", "router_fwd", "router_dx", "router_dw"};
+    "replica_allreduce", "router_fwd", "router_dx", "router_dw"};
 
 void timing_begin(int kid, hipStream_t st) {
   hipEvent_t e;

@@ -16,7 +16,7 @@ void launch_fill_i32(int32_t* p, int n, int32_t val, hipStream_t st);
 enum KernelId {
   K_FILL = 0, K_ROUTE, K_ROUTE_BWD, K_PLACE, K_CHUNK_COUNT, K_CHUNK_SCAN, K_CHUNK_RANK, K_GATHER,
   K_TILE_MAP, K_GEMM_FWD1, K_GEMM_FWD2, K_GEMM_BWD_DH, K_GEMM_BWD_DX, K_GEMM_WGRAD2, K_GEMM_WGRAD1,
-  K_COMBINE, K_COMBINE_BWD, K_DISPATCH_BWD, K_ADAM, K_DSWIGLU, K_REPLICA_AR, K_ROUTER_FWD, K_ROUTER_DX, K_ROUTER_DW, K_COUNT
+  K_COMBINE, K_COMBINE_BWD, K_DISPATCH_BWD, K_ADAM, K_REPLICA_AR, K_ROUTER_FWD, K_ROUTER_DX, K_ROUTER_DW, K_COUNT
 };
 extern bool g_timing;
 void timing_begin(int kid, hipStream_t st);
