@@ -102,6 +102,73 @@ def survival(args):
         prev = hist.clone()
 
 
+def extras(args):
+    """Kernel times of the entry points around the core path on --config: the router GEMM and
+    its backward, and the replica gradient path as the paper draws it (per-slot weight
+    gradients + intra-rank all-reduce) next to the fused per-class one.  One JSON line."""
+    import torch
+    import paper_2504_19925_amd as symi
+    import workloads as wl
+    from tests import harness as Hn
+
+    c = wl.get_config(args.config)
+    st = Hn.State(c)
+    s, cfg = st, st.cfg
+    X, logits, dY = Hn.draw_inputs(c, 0)
+    st.place_current()
+    st.forward(X, logits)
+    st.backward(dY, logits)
+    st.hist_prev.copy_(st.hist)          # placement that mimics this popularity: replicated classes
+    st.place_current()
+    st.forward(X, logits)
+    Wr, b = wl.make_router(c, 0, "cuda")
+    lg = torch.empty(c.T, c.E, dtype=torch.float32, device="cuda")
+    dWr = torch.empty(c.E, c.d, dtype=torch.float32, device="cuda")
+    db = torch.empty(c.E, dtype=torch.float32, device="cuda")
+    g1 = torch.empty(c.S_tot, 2 * c.f, c.d, dtype=torch.float32, device="cuda")
+    g2 = torch.empty(c.S_tot, c.d, c.f, dtype=torch.float32, device="cuda")
+
+    def router():
+        symi.symi_router_fwd(cfg, X, Wr, b, lg)
+        symi.symi_router_bwd(cfg, X, Wr, s.dlogits, dWr, db, s.dX, s.ws)
+
+    def fused():
+        symi.symi_expert_bwd(cfg, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
+                             s.dXp, s.dW1, s.dW2, s.ws)
+
+    def drawn():
+        symi.symi_expert_bwd_slots(cfg, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s,
+                                   s.W2s, s.dXp, g1, g2, s.ws)
+        symi.symi_replica_allreduce(cfg, s.first_slot, 1.0, g1, g2)
+
+    symi.symi_combine_bwd(cfg, dY, s.Yp, s.row_of_assign, s.gate, s.dYp, s.dgate)
+    symi.symi_set_overlap(False)
+    out = {"workload": c.name, "unit": "us per call, all launches of a kernel id summed", "steps": args.steps}
+    for fn in (router, fused, drawn):
+        for _ in range(2):
+            fn()
+        Hn.sync()
+        symi.symi_timing_reset()
+        symi.symi_timing_enable(True)
+        for _ in range(args.steps):
+            fn()
+        Hn.sync()
+        symi.symi_timing_enable(False)
+        got = {}
+        for kid in range(symi.symi_kernel_count()):
+            ms, n = symi.symi_timing_read(kid)
+            if n:
+                got[symi.symi_kernel_name(kid)] = round(ms / args.steps * 1e3, 1)
+        got["total"] = round(sum(got.values()), 1)
+        out[fn.__name__] = got
+    symi.symi_set_overlap(True)
+    w = 2 if c.dtype == "bf16" else 4
+    out["router_floor_us_at_8TBps"] = {"fwd": round(c.T * c.d * w / 8e6, 1),
+                                       "dx": round((2 * c.T * c.d * w + 4 * c.T * c.E) / 8e6, 1),
+                                       "dw": round((c.T * c.d * w + 4 * c.T * c.E) / 8e6, 1)}
+    print(json.dumps(out))
+
+
 def calibrate_copy():
     """A plain copy of known size, to scale the HBM counters: 8 copies of 1 GiB."""
     import torch
@@ -299,6 +366,9 @@ def main():
                     help="keep every kernel on one stream also in the timed region (symi_set_overlap(0))")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device copy (reference for the HBM traffic counters)")
+    ap.add_argument("--extras", action="store_true",
+                    help="time the router GEMM/backward and the per-slot replica gradient path on "
+                         "--config instead of the benchmark")
     ap.add_argument("--survival", type=float, default=None, metavar="CAPACITY_FACTOR",
                     help="print the token survival per iteration of --config under this capacity "
                          "factor (adaptive vs. uniform placement) instead of the benchmark")
@@ -308,6 +378,9 @@ def main():
         return
     if args.survival is not None:
         survival(args)
+        return
+    if args.extras:
+        extras(args)
         return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share of the path; --gpus must be 1 "
