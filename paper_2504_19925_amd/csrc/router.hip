@@ -3,9 +3,12 @@
 //   logits = X Wr^T + b          dWr = dlogits^T X,  db = sum_t dlogits,  dX += dlogits Wr
 // Three skinny products (one side is E <= 1024 wide) that share one small tiled kernel:
 // 128 x 128 output tile, 4 wavefronts of 64 x 64 (2 x 2 MFMA 32x32x16 bf16 tiles), reduction
-// step 32.  Operands pass through registers into LDS (rows padded to 80 bytes) so that either
-// side may be reduction-contiguous (16-byte loads) or reduction-strided (8 coalesced
-// scalar loads), bf16 or fp32 in memory; many workgroups per compute unit hide the latency.
+// step 64.  Operands pass through registers into LDS (rows padded to 144 bytes; the next
+// step's global loads are in flight while the current one feeds the MFMAs) so that either
+// side may be bf16 or fp32 in memory and reduction-contiguous (LDS tile [row][k], fragments
+// are plain 16-byte reads) or reduction-strided (LDS tile [k][row] as in memory, fragments come
+// from the transposing LDS read ds_read_b64_tr_b16); several workgroups per compute unit hide
+// the latency.
 // The weight gradient's reduction runs over all T tokens: it is cut into chunks of 512
 // tokens whose partial products are summed by a second kernel in a fixed order.
 // fp32 configurations take a plain FMA kernel (one output per thread) instead.
@@ -17,8 +20,11 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 rbf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float rfloatx16;
 
 constexpr int RT = 128;        // tile rows and columns
-constexpr int RK = 32;         // reduction step
-constexpr int RLD = RK + 8;    // padded LDS row (elements)
+constexpr int RK = 64;         // reduction step
+constexpr int RLD = RK + 8;    // padded LDS row of a [row][k] tile (elements; 144 B)
+constexpr int RLS = RT + 32;   // padded LDS row of a [k][row] tile (320 B: four k-rows cover 64 banks)
+constexpr int RTILE = RT * RLD > RK * RLS ? RT * RLD : RK * RLS;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short rshortx4;
 constexpr int RCHUNK = 512;    // tokens per partial weight gradient
 
 enum { R_FWD = 0, R_DX = 1, R_DW = 2 };
@@ -65,49 +71,33 @@ __device__ __forceinline__ uint4 load8(const void* src, long long ld, int r, int
   return pack8(v);
 }
 
-// Fill of a reduction-strided operand (memory [k][r], r contiguous): thread -> (k-row, 8
-// consecutive r), one vector load (16 bytes bf16 / 32 bytes fp32), then the 8 values are
-// scattered into the [r][k] LDS tile.  512 pieces per 32-deep step, two per thread.
+// A reduction-strided operand (memory [k][r], r contiguous) is fetched with one vector load per
+// (k-row, 8 consecutive r) and stored to its [k][r] LDS tile as it is.
 template <bool F32>
-__device__ __forceinline__ void fill_strided(uint16_t* tile, const void* src, long long ld, int r0,
-                                             int rows, int k0, int kend, int tid) {
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int u = tid + 256 * h;
-    const int kl = u >> 4, r8 = (u & 15) * 8;
-    const int k = k0 + kl, r = r0 + r8;
-    uint16_t v[8];
-    if (k < kend && r + 7 < rows) {
-      if (F32) {
-        const float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + (long long)k * ld + r);
-        const float4 b = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + (long long)k * ld + r + 4);
-        const float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = f32_to_bf16(f[i]);
-      } else {
-        const uint4 q = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src) + (long long)k * ld + r);
-        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { v[2 * i] = (uint16_t)(w[i] & 0xffffu); v[2 * i + 1] = (uint16_t)(w[i] >> 16); }
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        v[i] = 0;
-        if (k < kend && r + i < rows)
-          v[i] = F32 ? f32_to_bf16(static_cast<const float*>(src)[(long long)k * ld + r + i])
-                     : static_cast<const uint16_t*>(src)[(long long)k * ld + r + i];
-      }
+__device__ __forceinline__ uint4 load8_strided(const void* src, long long ld, int r, int rows, int k, int kend) {
+  if (k >= kend || r >= rows) return make_uint4(0, 0, 0, 0);
+  if (r + 7 < rows && (ld & (F32 ? 3 : 7)) == 0) {
+    if (F32) {
+      const float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + (long long)k * ld + r);
+      const float4 c = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + (long long)k * ld + r + 4);
+      return make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(c.x, c.y), pack_bf16x2(c.z, c.w));
     }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) tile[(r8 + i) * RLD + kl] = v[i];
+    return *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src) + (long long)k * ld + r);
   }
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    v[i] = 0.f;
+    if (r + i < rows)
+      v[i] = F32 ? static_cast<const float*>(src)[(long long)k * ld + r + i]
+                 : bf16_to_f32(static_cast<const uint16_t*>(src)[(long long)k * ld + r + i]);
+  }
+  return pack8(v);
 }
-
 template <int MODE>
 __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[RT * RLD];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[RT * RLD];
+  __shared__ __attribute__((aligned(16))) uint16_t As[RTILE];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[RTILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   // output rows M, columns N, reduction range [kbeg, kend)
@@ -127,38 +117,63 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // per operand and step 128 rows x 64 reduction indices = 1024 pieces of 8, four per thread.
+  // Reduction-contiguous operands: piece u -> (row u/8, k-piece u%8), committed with one 16-byte
+  // LDS store at [row][k]; strided ones: piece u -> (k-row u/16, rows 8*(u%16) ..), one 16-byte
+  // LDS store at [k][row].
+  constexpr bool A_CONTIG = MODE != R_DW, B_CONTIG = MODE == R_FWD;
+  uint4 ra[4], rb[4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const int u = tid + 256 * h;
+      if (MODE == R_FWD) ra[h] = load8<true, false>(p.X, p.d, m0 + (u >> 3), M, k0 + 8 * (u & 7), kend);
+      else if (MODE == R_DX) ra[h] = load8<true, true>(p.dl, p.E, m0 + (u >> 3), M, k0 + 8 * (u & 7), kend);
+      else ra[h] = load8_strided<true>(p.dl, p.E, m0 + 8 * (u & 15), M, k0 + (u >> 4), kend);
+      if (MODE == R_FWD) rb[h] = load8<true, false>(p.Wr, p.d, n0 + (u >> 3), N, k0 + 8 * (u & 7), kend);
+      else rb[h] = load8_strided<false>(MODE == R_DX ? p.Wr : p.X, p.d, n0 + 8 * (u & 15), N, k0 + (u >> 4), kend);
+    }
+  };
+  auto commit = [&]() {
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const int u = tid + 256 * h;
+      if (A_CONTIG) *reinterpret_cast<uint4*>(&As[(u >> 3) * RLD + 8 * (u & 7)]) = ra[h];
+      else *reinterpret_cast<uint4*>(&As[(u >> 4) * RLS + 8 * (u & 15)]) = ra[h];
+      if (B_CONTIG) *reinterpret_cast<uint4*>(&Bs[(u >> 3) * RLD + 8 * (u & 7)]) = rb[h];
+      else *reinterpret_cast<uint4*>(&Bs[(u >> 4) * RLS + 8 * (u & 15)]) = rb[h];
+    }
+  };
+
+  if (kbeg < kend) fetch(kbeg);
   for (int k0 = kbeg; k0 < kend; k0 += RK) {
-    // fill: per operand 128 rows x 32 reduction indices.  Reduction-contiguous operands:
-    // thread -> (row, 8 consecutive k), 16-byte LDS store; strided ones: see fill_strided.
-    if (MODE == R_DW) {
-      fill_strided<true>(As, p.dl, p.E, m0, M, k0, kend, tid);
-    } else {
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int u = tid + 256 * h, r = u >> 2, piece = u & 3;
-        const uint4 v = MODE == R_FWD ? load8<true, false>(p.X, p.d, m0 + r, M, k0 + 8 * piece, kend)
-                                      : load8<true, true>(p.dl, p.E, m0 + r, M, k0 + 8 * piece, kend);
-        *reinterpret_cast<uint4*>(&As[r * RLD + 8 * piece]) = v;
-      }
-    }
-    if (MODE == R_FWD) {
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int u = tid + 256 * h, r = u >> 2, piece = u & 3;
-        *reinterpret_cast<uint4*>(&Bs[r * RLD + 8 * piece]) =
-            load8<true, false>(p.Wr, p.d, n0 + r, N, k0 + 8 * piece, kend);
-      }
-    } else {
-      fill_strided<false>(Bs, MODE == R_DX ? p.Wr : p.X, p.d, n0, N, k0, kend, tid);
-    }
+    commit();
     __syncthreads();
+    if (k0 + RK < kend) fetch(k0 + RK);   // in flight while this step feeds the MFMAs
 #pragma unroll
     for (int ks = 0; ks < RK / 16; ++ks) {
       rbf16x8 af[2], bfr[2];
+      // [row][k] tile: lane -> row lane%32, 8 k at 16*ks + 8*(lane/32).  [k][row] tile: lane =
+      // 16*g + jj addresses k-row 16*ks + 8*(g>>1) + jj/4 (+4 for the second half), the 8-byte
+      // piece jj%4 of rows 16*(g&1) ..; the transposing read hands it row lane%32's 4 + 4 k-values
+      auto frag = [&](const uint16_t* tile, bool contig, int rbase) -> rbf16x8 {
+        if (contig)
+          return *reinterpret_cast<const rbf16x8*>(&tile[(rbase + (lane & 31)) * RLD + ks * 16 + 8 * (lane >> 5)]);
+        const int g = lane >> 4, jj = lane & 15;
+        const uint16_t* q = tile + (16 * ks + 8 * (g >> 1) + (jj >> 2)) * RLS + rbase + 16 * (g & 1) + 4 * (jj & 3);
+        const rshortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) rshortx4*)((void __attribute__((address_space(3)))*)(q)));
+        const rshortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) rshortx4*)((void __attribute__((address_space(3)))*)(q + 4 * RLS)));
+        union { rshortx4 h[2]; rbf16x8 v; } u;
+        u.h[0] = lo;
+        u.h[1] = hi;
+        return u.v;
+      };
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        af[i] = *reinterpret_cast<const rbf16x8*>(&As[(wm * 64 + i * 32 + (lane & 31)) * RLD + ks * 16 + 8 * (lane >> 5)]);
-        bfr[i] = *reinterpret_cast<const rbf16x8*>(&Bs[(wn * 64 + i * 32 + (lane & 31)) * RLD + ks * 16 + 8 * (lane >> 5)]);
+        af[i] = frag(As, A_CONTIG, wm * 64 + i * 32);
+        bfr[i] = frag(Bs, B_CONTIG, wn * 64 + i * 32);
       }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
