@@ -275,7 +275,9 @@ def run_gpu(args):
     else:
         roof = {"bound": "hbm", "achieved": round(by / avg_s / 1e9, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(by / avg_s / 1e9 / HBM_PEAK_GBS, 4)}
-    roof.update({"kernel": dom, "avg_us": round(avg_s * 1e6, 2), "traffic": measured_traffic(c.name, dom),
+    roof.update({"kernel": dom, "avg_us": round(avg_s * 1e6, 2),
+                 "measured": "HIP events, second pass of the same steps with one kernel at a time",
+                 "traffic": measured_traffic(c.name, dom),
                  "algorithmic_bytes": by, "algorithmic_flops": fl})
 
     out = {

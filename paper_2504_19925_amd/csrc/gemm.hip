@@ -16,7 +16,8 @@
 // two slots.  The last two have a variable reduction length (the rows of a class).
 //
 // The MFMA is issued with the weight tile as its first operand, so a lane ends up with 4
-// consecutive output columns of one output row; a half-wave swap widens that to 8.
+// consecutive output columns of one output row; the epilogue turns the blocks around through
+// LDS so that stores cover whole cache lines.
 #include <type_traits>
 
 #include "common.h"
@@ -116,8 +117,9 @@ __global__ __launch_bounds__(256) void tile_map_kernel(const int32_t* __restrict
 //     the LDS serves per cycle (4 k-rows x 64 B) then fall into 64 distinct banks;
 //     fragments come from the transposing LDS read (ds_read_b64_tr_b16), which hands
 //     lane j of a 16-lane group the four k-values of column j.
-// A direct-to-LDS load cannot zero-fill, so lanes outside the operand (row or column
-// beyond the tile's extent, reduction index beyond K) load from a block of zeros.
+// A direct-to-LDS load cannot zero-fill: rows or columns beyond the tile's extent are clamped
+// to a valid one (they only reach outputs that are never stored), reduction indices beyond K
+// load from a block of zeros.
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int GT = 256;
 
