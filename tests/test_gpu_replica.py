@@ -61,3 +61,40 @@ def test_replica_gradient_path(name, it, scale):
     check_close("rep_vs_fused_dW2", Hn.npf(g2[first]), scale * Hn.npf(st.dW2).astype(np.float64), c.dtype,
                 group_axis=0, log=log)
     print("[err] " + " ".join(f"{k}:max={v['max']:.2e}" for k, v in log.items()), flush=True)
+
+
+def test_replica_path_full_size_c2_matches_fused_path():
+    """Config c2 at full size, placement mimicking the previous iteration (hot classes
+    replicated over many slots): after the all-reduce every slot of a class holds the class
+    gradient that the fused path computes (same products, different summation order), and
+    slots without rows contributed zeros."""
+    import workloads as wl
+    c = wl.get_config("c2")
+    st = Hn.State(c)
+    X0, logits0, dY0 = Hn.draw_inputs(c, 0)
+    st.place_current()
+    st.forward(X0, logits0)
+    st.hist_prev.copy_(st.hist)
+    st.place_current()                                  # replicas proportional to iteration 0's popularity
+    st.forward(X0, logits0)
+    st.backward(dY0, logits0)
+    s, cfg = st, st.cfg
+    g1 = torch.full((c.S_tot, 2 * c.f, c.d), float("nan"), dtype=torch.float32, device="cuda")
+    g2 = torch.full((c.S_tot, c.d, c.f), float("nan"), dtype=torch.float32, device="cuda")
+    symi.symi_expert_bwd_slots(cfg, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
+                               s.dXp, g1, g2, s.ws)
+    Hn.sync()
+    off = s.slot_offsets.cpu().numpy()
+    assert int(s.counts.max()) > 4                      # the hot classes really are replicated
+    for q in np.nonzero(np.diff(off) == 0)[0][:8]:
+        assert not g1[q].any() and not g2[q].any()
+    symi.symi_replica_allreduce(cfg, s.first_slot, 1.0, g1, g2)
+    Hn.sync()
+    pl = s.placement.long()
+    for e in torch.unique(pl).tolist()[:6] + [int(s.counts.argmax())]:
+        for q in torch.nonzero(pl == e).flatten().tolist()[:3]:
+            a1, b1 = g1[q].double(), st.dW1[e].double()
+            a2, b2 = g2[q].double(), st.dW2[e].double()
+            scale1, scale2 = b1.abs().max().item() + 1e-30, b2.abs().max().item() + 1e-30
+            assert (a1 - b1).abs().max().item() / scale1 <= 1e-5
+            assert (a2 - b2).abs().max().item() / scale2 <= 1e-5
