@@ -7,13 +7,18 @@
  *   forward    symi_route -> symi_dispatch (or symi_dispatch_capacity) -> symi_expert_fwd -> symi_combine
  *   backward   symi_combine_bwd -> symi_expert_bwd -> symi_dispatch_bwd -> symi_route_bwd
  *   optimizer  symi_place (next placement, Algorithm 1) -> symi_adam_to_replicas
+ *   optional   symi_router_fwd before symi_route, symi_router_bwd after symi_route_bwd;
+ *              symi_expert_bwd_slots + symi_replica_allreduce instead of symi_expert_bwd;
+ *              host helpers for the multi-rank plan at the end of this file
  *
  * Conventions
  *   - Every function returns 0 (SYMI_OK) or a negative error code; symi_last_error()
  *     returns a description of the most recent failure on the calling thread.
  *   - Unless a parameter says "host", every pointer is a DEVICE pointer owned by the
  *     caller, valid until the work enqueued on `stream` has finished.  The library
- *     allocates nothing and never synchronises with the host inside these calls.
+ *     allocates no memory and never synchronises with the host inside these calls (the
+ *     only objects it creates are one helper stream and three events per device, at the
+ *     first symi_expert_bwd call; see symi_set_overlap).  Calls are not thread-safe.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - `cfg` and `hp` are HOST pointers, read during the call only.
  *   - Activations and slot weights are fp32 or bf16 according to cfg->dtype; routing
