@@ -247,3 +247,16 @@ def test_backward_on_two_streams_equals_backward_on_one():
     for other in outs[1:]:
         for a, b in zip(outs[0], other):
             assert torch.equal(a, b)
+
+
+def test_shape_limits_of_the_interface():
+    """The largest class, choice and slot counts the interface accepts (E = 1024, k = 16,
+    S_tot = 4096), two iterations so that the second placement is a replicated one."""
+    base = wl.scaled(wl.get_config("c1"), dtype="bf16")
+    c = wl.scaled(base, T=700, E=1024, k=16, S_tot=4096, N=4, d=64, f=64, router_matmul=False,
+                  bias="zipf", zipf_s=0.5)
+    st = Hn.State(c, shard=1)
+    for it in range(2):
+        X, logits, dY = Hn.draw_inputs(c, it)
+        check_iteration(st, X, logits, dY)
+        st.hist_prev.copy_(st.hist)
