@@ -667,15 +667,32 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
 
   float acc[4][4] = {};
   const int ty = tid >> 4, tx = tid & 15;  // rows ty*4.., cols tx + 16*c (FWD1 pairs gate/up)
-  for (int k0 = 0; k0 < K; k0 += FK) {
-    for (int e = tid; e < FB * FK; e += 256) {
-      // walk the operand along its contiguous index for coalescing
+  // each thread carries 4 + 4 elements of a step from memory to LDS; the elements of the next
+  // step are fetched into registers before the current step's FMAs, so their latency hides
+  // behind them.  Operands are walked along their contiguous index for coalescing.
+  float na[4], nb[4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const int e = tid + 256 * h;
       const int ai = A_KC ? e / FK : e % FB, ak = A_KC ? e % FK : e / FB;
-      As[ak][ai] = a_at(ai, k0 + ak);
+      na[h] = a_at(ai, k0 + ak);
       const int bj = B_KC ? e / FK : e % FB, bk = B_KC ? e % FK : e / FB;
-      Bs[bk][bj] = b_at(bj, k0 + bk);
+      nb[h] = b_at(bj, k0 + bk);
+    }
+  };
+  if (K > 0) fetch(0);
+  for (int k0 = 0; k0 < K; k0 += FK) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const int e = tid + 256 * h;
+      const int ai = A_KC ? e / FK : e % FB, ak = A_KC ? e % FK : e / FB;
+      As[ak][ai] = na[h];
+      const int bj = B_KC ? e / FK : e % FB, bk = B_KC ? e % FK : e / FB;
+      Bs[bk][bj] = nb[h];
     }
     __syncthreads();
+    if (k0 + FK < K) fetch(k0 + FK);
     // two-level summation: each 16-deep partial sum is formed on its own and then added,
     // which keeps the rounding error of long reductions (weight gradients) near sqrt(K/16)
     float part[4][4] = {};
