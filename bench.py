@@ -206,12 +206,12 @@ def run_gpu(args):
         st.first_slot, st.first_slot_next = st.first_slot_next, st.first_slot
         st.placement, st.placement_next = st.placement_next, st.placement
 
-    def timed(n_steps, first):
-        """n_steps steps with a HIP event pair around every launch; returns ms per step and
-        {kernel: (average ms per launch, launches)}."""
+    def timed(n_steps, first, events):
+        """n_steps steps, optionally with a HIP event pair around every launch; returns ms per
+        step and {kernel: (average ms per launch, launches)}."""
         Hn.sync()
         symi.symi_timing_reset()
-        symi.symi_timing_enable(True)
+        symi.symi_timing_enable(events)
         Hn.sync()
         t0 = time.perf_counter()
         for i in range(n_steps):
@@ -230,13 +230,15 @@ def run_gpu(args):
     symi.symi_set_overlap(not args.no_overlap)
     for i in range(args.warmup):
         step(i)
-    # the timed region: the library as it ships (the backward's two chains of products may
-    # share the chip on two streams, so kernel durations overlap there)
-    ms_per_step, times_region = timed(args.steps, args.warmup)
-    # per-kernel durations and the roofline come from the same steps run again with one kernel
-    # at a time on the stream, which is also what the committed rocprofv3 summary shows
+    # the timed region: the library as it ships, nothing but the K steps between two
+    # synchronisations (no events: a pair around each of the ~20 launches of a step costs 6 % on
+    # c2; the backward's two chains of products may share the chip on two streams)
+    ms_per_step, _ = timed(args.steps, args.warmup, False)
+    # per-kernel durations and the roofline come from the same steps run again with HIP events
+    # around every launch and one kernel at a time on the stream, which is also what the
+    # committed rocprofv3 summary shows
     symi.symi_set_overlap(False)
-    ms_serial, times = timed(args.steps, args.warmup)
+    ms_serial, times = timed(args.steps, args.warmup, True)
     symi.symi_set_overlap(not args.no_overlap)
     w = 2 if c.dtype == "bf16" else 4
 
@@ -276,7 +278,7 @@ def run_gpu(args):
         roof = {"bound": "hbm", "achieved": round(by / avg_s / 1e9, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(by / avg_s / 1e9 / HBM_PEAK_GBS, 4)}
     roof.update({"kernel": dom, "avg_us": round(avg_s * 1e6, 2),
-                 "measured": "HIP events, second pass of the same steps with one kernel at a time",
+                 "measured": "HIP events around every launch, second pass of the same steps, one kernel at a time",
                  "traffic": measured_traffic(c.name, dom),
                  "algorithmic_bytes": by, "algorithmic_flops": fl})
 
@@ -294,8 +296,8 @@ def run_gpu(args):
         "roofline": roof,
         "fwd_bwd_tokens_per_s": round(c.T / (fwd_bwd_ms * 1e-3), 1),
         "gpu_kernel_ms_per_step": round(gpu_ms, 4),
-        "ms_per_step_one_kernel_at_a_time": round(ms_serial, 4),
-        "kernel_table": "measured in a second pass of the same steps with symi_set_overlap(0)",
+        "ms_per_step_second_pass": round(ms_serial, 4),
+        "kernel_table": "second pass of the same steps: HIP events around every launch, symi_set_overlap(0)",
         "nonempty_slots_mean": round(mean_nonempty, 2),
         "kernels": kernels,
     }

@@ -260,3 +260,41 @@ def test_shape_limits_of_the_interface():
         X, logits, dY = Hn.draw_inputs(c, it)
         check_iteration(st, X, logits, dY)
         st.hist_prev.copy_(st.hist)
+
+
+def test_forward_backward_under_graph_capture():
+    """The calls can be captured into a HIP graph (including the helper-stream fork/join of the
+    backward): every replay, with eager work and synchronisations in between, reproduces the
+    eager results bit for bit."""
+    c = _small("c2")
+    st = Hn.State(c)
+    X, logits, dY = Hn.draw_inputs(c, 0)
+    st.place_current()
+    st.forward(X, logits)
+    st.backward(dY, logits)          # eager reference (also creates the helper stream outside the capture)
+    Hn.sync()
+    outs = (st.Y, st.dX, st.dW1, st.dW2, st.dgate, st.dlogits, st.hist, st.row_of_assign, st.slot_offsets)
+    want = [t.clone() for t in outs]
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        st.forward(X, logits)
+        st.backward(dY, logits)
+        torch.cuda.current_stream().synchronize()
+        g.capture_begin()
+        st.forward(X, logits)
+        st.backward(dY, logits)
+        g.capture_end()
+    torch.cuda.current_stream().wait_stream(s)
+    Hn.sync()
+    scratch = torch.empty(1 << 20, device="cuda")
+    for rep in range(4):
+        for t in outs:
+            t.zero_() if t.dtype == torch.int32 else t.fill_(float("nan"))
+        scratch.normal_()            # eager work between the replays
+        Hn.sync()
+        g.replay()
+        Hn.sync()
+        for t, w in zip(outs, want):
+            assert torch.equal(t, w), f"replay {rep}"
