@@ -207,6 +207,20 @@ static void route_shape(int E, int& G, int& NV) {
   NV = need <= 1 ? 1 : (need <= 2 ? 2 : 4);
 }
 
+// The forward kernel spends its time in the k selection rounds: few lanes per token (a short
+// butterfly) with up to 32 values each, scanned locally, cost a third of the instructions of
+// one float4 per lane.
+static void route_fwd_shape(int E, int T, int& G, int& NV) {
+  const int vecs = (E + 3) / 4;
+  G = 1;
+  while (G * 8 < vecs && G < 64) G <<= 1;
+  // a small batch is spread over more lanes per token instead, so that the chip is filled:
+  // at least 512 workgroups of (256 / G) tokens, as long as a lane still has a float4
+  while (G < vecs && G < 64 && (long long)T * G < 512LL * ROUTE_THREADS) G <<= 1;
+  const int need = (vecs + G - 1) / G;
+  NV = need <= 1 ? 1 : (need <= 2 ? 2 : (need <= 4 ? 4 : 8));
+}
+
 static int route_grid(int T, int G) {
   const int tpb = (ROUTE_THREADS / 64) * (64 / G);
   int grid = cdiv(T, tpb);
@@ -226,15 +240,17 @@ extern "C" int symi_route(const symi_cfg* cfg, const float* logits, int32_t* idx
   launch_fill_i32(hist, E, 0, st);
   if (cfg->T > 0) {
     int G, NV;
-    route_shape(E, G, NV);
+    route_fwd_shape(E, cfg->T, G, NV);
     const int grid = route_grid(cfg->T, G);
     const size_t sh = (size_t)E * sizeof(int32_t);
     if (NV == 1)
       SYMI_TIMED(K_ROUTE, st, (route_kernel<1><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
     else if (NV == 2)
       SYMI_TIMED(K_ROUTE, st, (route_kernel<2><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
-    else
+    else if (NV == 4)
       SYMI_TIMED(K_ROUTE, st, (route_kernel<4><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
+    else
+      SYMI_TIMED(K_ROUTE, st, (route_kernel<8><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
   }
   SYMI_LAUNCH_CHECK("symi_route");
   return SYMI_OK;
