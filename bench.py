@@ -28,11 +28,12 @@ MFMA_BF16_PEAK_TF = 2500.0     # dense bf16 MFMA
 FP32_VEC_PEAK_TF = 157.3       # fp32 vector FMA
 
 
-def kernel_work(c, w, nonempty_slots):
+def kernel_work(c, w, nonempty_slots, grad_classes):
     """Algorithmic (flops, bytes) of one launch of each kernel for workload c."""
     T, E, k, d, f, S, N = c.T, c.E, c.k, c.d, c.f, c.S_tot, c.N
     A = T * k
     Sn = nonempty_slots
+    Eg = grad_classes      # classes whose weight gradient is written by the backward and read by Adam
     nblk = (A + 1023) // 1024
     per = 3 * d * f // N
     return {
@@ -46,12 +47,12 @@ def kernel_work(c, w, nonempty_slots):
         "gemm_fwd2": (2 * A * f * d, Sn * d * f * w + A * f * w + A * d * w),
         "gemm_bwd_dh": (2 * A * d * f, Sn * d * f * w + A * d * w + 4 * A * f * w),
         "gemm_bwd_dx": (2 * A * 2 * f * d, Sn * 2 * f * d * w + A * 2 * f * w + A * d * w),
-        "gemm_wgrad2": (2 * A * d * f, A * d * w + A * f * w + E * d * f * 4),
-        "gemm_wgrad1": (2 * A * 2 * f * d, A * 2 * f * w + A * d * w + E * 2 * f * d * 4),
+        "gemm_wgrad2": (2 * A * d * f, A * d * w + A * f * w + Eg * d * f * 4),
+        "gemm_wgrad1": (2 * A * 2 * f * d, A * 2 * f * w + A * d * w + Eg * 2 * f * d * 4),
         "combine": (0, A * d * w + T * d * w + 8 * A),
         "combine_bwd": (0, T * d * w + 2 * A * d * w + 12 * A),
         "dispatch_bwd": (0, A * d * w + T * d * w + 4 * A),
-        "adam_to_replicas": (0, E * per * 28 + S * per * w),
+        "adam_to_replicas": (0, E * per * 24 + Eg * per * 4 + S * per * w),
     }
 
 
@@ -190,6 +191,7 @@ def run_gpu(args):
     c = wl.get_config(args.config)
     torch.cuda.set_device(0)
     st = Hn.State(c, shard=0)
+    st.active_grads = not args.dense_grads
     iters = max(c.iters, 1)
     inputs = [Hn.draw_inputs(c, it) for it in range(iters)]
     adam, _ = Hn.make_adam()
@@ -243,15 +245,17 @@ def run_gpu(args):
     w = 2 if c.dtype == "bf16" else 4
 
     # slots that actually hold rows (their weights are the ones a step must read)
-    nonempty = []
+    nonempty, active = [], []
     for i in range(iters):
         step(args.warmup + args.steps + i)
         Hn.sync()
         so = st.slot_offsets.cpu()
         nonempty.append(int((so[1:] > so[:-1]).sum()))
+        active.append(int((st.hist > 0).sum()))
     mean_nonempty = sum(nonempty) / len(nonempty)
+    mean_active = sum(active) / len(active)
 
-    work = kernel_work(c, w, mean_nonempty)
+    work = kernel_work(c, w, mean_nonempty, c.E if args.dense_grads else mean_active)
     peak_tf = MFMA_BF16_PEAK_TF if c.dtype == "bf16" else FP32_VEC_PEAK_TF
     kernels = {}
     for name, (avg_ms, n) in times.items():
@@ -292,13 +296,18 @@ def run_gpu(args):
         "dtype": c.dtype, "data": "synthetic",
         "config": {"workload": f"{c.name}: {c.dtype} E={c.E} top-{c.k} d={c.d} f={c.f} T={c.T} "
                                f"S_tot={c.S_tot} N={c.N} (1 shard of {c.N}), {iters} iteration(s) cycled",
-                   "step": "route+dispatch+expert_fwd+combine+backward+place+adam_to_replicas"},
+                   "step": "route+dispatch+expert_fwd+combine+backward+place+adam_to_replicas",
+                   "weight_gradients": "all classes, zeros written and read for those without tokens"
+                   if args.dense_grads else
+                   "classes with tokens only (symi_expert_bwd_active + symi_adam_to_replicas_active: "
+                   "same master weights, moments and slots, bit for bit)"},
         "roofline": roof,
         "fwd_bwd_tokens_per_s": round(c.T / (fwd_bwd_ms * 1e-3), 1),
         "gpu_kernel_ms_per_step": round(gpu_ms, 4),
         "ms_per_step_second_pass": round(ms_serial, 4),
         "kernel_table": "second pass of the same steps: HIP events around every launch, symi_set_overlap(0)",
         "nonempty_slots_mean": round(mean_nonempty, 2),
+        "classes_with_tokens_mean": round(mean_active, 2),
         "kernels": kernels,
     }
     return out, c
@@ -368,6 +377,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep every kernel on one stream also in the timed region (symi_set_overlap(0))")
+    ap.add_argument("--dense-grads", action="store_true",
+                    help="symi_expert_bwd / symi_adam_to_replicas (zero gradients of classes without "
+                         "tokens written and read back) instead of the *_active pair")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device copy (reference for the HBM traffic counters)")
     ap.add_argument("--extras", action="store_true",

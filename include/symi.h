@@ -197,6 +197,28 @@ int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* Wr, const fl
  * batches); symi_set_overlap(0) keeps every kernel on `stream` itself, (1) is the default. */
 int symi_set_overlap(int on);
 
+/* The same two calls for a batch that leaves many classes without tokens.  A rank of the
+ * paper only ever forms gradients for the classes it hosts (Sec. 4.1; Algorithm 2 collects a
+ * shard from a hosting rank), and a class no token chose contributes a zero gradient to the
+ * optimizer step (Sec. 3.2 steps 4-6).  With one GPU standing in for all slots, writing
+ * those zeros and reading them back is traffic the method does not have:
+ *   symi_expert_bwd_active = symi_expert_bwd, except that dW1_class[e], dW2_class[e] of a class
+ *     e without rows (slot_offsets[first_slot[e+1]] == slot_offsets[first_slot[e]]) are left
+ *     UNTOUCHED (whatever the buffers held stays there);
+ *   symi_adam_to_replicas_active = symi_adam_to_replicas, except that the gradient of such a
+ *     class is taken as zero and its memory is not read.  slot_offsets [S_tot+1] and
+ *     first_slot [E+1] are those of the iteration the gradients come from (device pointers).
+ * Together they give bit for bit the master_w, m, v and slots of the plain pair.          */
+int symi_expert_bwd_active(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
+                           const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
+                           const void* W1_slots, const void* W2_slots, void* dXp,
+                           float* dW1_class, float* dW2_class, void* ws, void* stream);
+int symi_adam_to_replicas_active(const symi_cfg* cfg, const symi_adam* hp, const float* dW1_class,
+                                 const float* dW2_class, float* master_w, float* m, float* v,
+                                 const int32_t* slot_offsets, const int32_t* first_slot,
+                                 const int32_t* first_slot_next, void* W1_slots, void* W2_slots,
+                                 void* stream);
+
 /* The replica gradient path as the paper draws it (Sec. 4.1, Fig. 7), as an alternative to
  * symi_expert_bwd's fused per-class sum.  symi_expert_bwd_slots is symi_expert_bwd with one
  * weight gradient per replica SLOT, summed over that slot's own rows only:

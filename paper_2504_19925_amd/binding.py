@@ -19,7 +19,7 @@ EXPORTS = [
     "symi_dispatch_capacity", "symi_dispatch_bwd", "symi_expert_fwd",
     "symi_expert_bwd", "symi_combine", "symi_combine_bwd", "symi_adam_to_replicas",
     "symi_timing_enable", "symi_timing_reset", "symi_timing_read", "symi_kernel_count",
-    "symi_kernel_name", "symi_expert_bwd_slots", "symi_set_overlap", "symi_replica_allreduce", "symi_router_fwd", "symi_router_bwd",
+    "symi_kernel_name", "symi_expert_bwd_slots", "symi_expert_bwd_active", "symi_adam_to_replicas_active", "symi_set_overlap", "symi_replica_allreduce", "symi_router_fwd", "symi_router_bwd",
     "symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost",
 ]
 
@@ -91,12 +91,15 @@ def lib():
             "symi_expert_fwd": [cfgp, vp, ip, vp, vp, vp, vp, vp, vp, vp],
             "symi_expert_bwd": [cfgp, vp, vp, vp, vp, ip, ip, vp, vp, vp, fp, fp, vp, vp],
             "symi_expert_bwd_slots": [cfgp, vp, vp, vp, vp, ip, ip, vp, vp, vp, fp, fp, vp, vp],
+            "symi_expert_bwd_active": [cfgp, vp, vp, vp, vp, ip, ip, vp, vp, vp, fp, fp, vp, vp],
             "symi_replica_allreduce": [cfgp, ip, ctypes.c_float, fp, fp, vp],
             "symi_router_fwd": [cfgp, vp, vp, fp, fp, vp],
             "symi_router_bwd": [cfgp, vp, vp, fp, fp, fp, vp, vp, vp],
             "symi_combine": [cfgp, vp, ip, fp, vp, vp],
             "symi_combine_bwd": [cfgp, vp, vp, ip, fp, vp, fp, vp],
             "symi_adam_to_replicas": [cfgp, ctypes.POINTER(SymiAdam), fp, fp, fp, fp, fp, ip, vp, vp, vp],
+            "symi_adam_to_replicas_active": [cfgp, ctypes.POINTER(SymiAdam), fp, fp, fp, fp, fp, ip, ip, ip,
+                                             vp, vp, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -313,19 +316,31 @@ def symi_expert_fwd(cfg, Xp, slot_offsets, W1_slots, W2_slots, UV, H, Yp, ws):
         _stream()), "symi_expert_fwd")
 
 
-def symi_expert_bwd(cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots, W2_slots, dXp,
-                    dW1_class, dW2_class, ws):
+def _expert_bwd_class(name, cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots, W2_slots, dXp,
+                      dW1_class, dW2_class, ws):
     dt = cfg.torch_dtype
     nw = cfg.S_tot * cfg.d * cfg.f
     ne = cfg.E * cfg.d * cfg.f
-    _check(lib().symi_expert_bwd(
+    _check(getattr(lib(), name)(
         ctypes.byref(cfg), _dev(dYp, dt, "dYp", cfg.A * cfg.d), _dev(Xp, dt, "Xp", cfg.A * cfg.d),
         _dev(UV, dt, "UV", cfg.A * 2 * cfg.f), _dev(H, dt, "H", cfg.A * cfg.f),
         _dev(slot_offsets, I32, "slot_offsets", cfg.S_tot + 1),
         _dev(first_slot, I32, "first_slot", cfg.E + 1), _dev(W1_slots, dt, "W1_slots", 2 * nw),
         _dev(W2_slots, dt, "W2_slots", nw), _dev(dXp, dt, "dXp", cfg.A * cfg.d),
         _dev(dW1_class, F32, "dW1_class", 2 * ne), _dev(dW2_class, F32, "dW2_class", ne),
-        _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), "symi_expert_bwd")
+        _dev(ws, torch.uint8, "ws", symi_workspace_bytes(cfg)), _stream()), name)
+
+
+def symi_expert_bwd(cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots, W2_slots, dXp,
+                    dW1_class, dW2_class, ws):
+    _expert_bwd_class("symi_expert_bwd", cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots,
+                      W2_slots, dXp, dW1_class, dW2_class, ws)
+
+
+def symi_expert_bwd_active(cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots, W2_slots, dXp,
+                           dW1_class, dW2_class, ws):
+    _expert_bwd_class("symi_expert_bwd_active", cfg, dYp, Xp, UV, H, slot_offsets, first_slot,
+                      W1_slots, W2_slots, dXp, dW1_class, dW2_class, ws)
 
 
 def symi_expert_bwd_slots(cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots, W2_slots, dXp,
@@ -401,3 +416,20 @@ def symi_adam_to_replicas(cfg, hp, dW1_class, dW2_class, master_w, m, v, first_s
         _dev(first_slot_next, I32, "first_slot_next", cfg.E + 1),
         _dev(W1_slots, dt, "W1_slots", 2 * nw), _dev(W2_slots, dt, "W2_slots", nw), _stream()),
         "symi_adam_to_replicas")
+
+
+def symi_adam_to_replicas_active(cfg, hp, dW1_class, dW2_class, master_w, m, v, slot_offsets,
+                                 first_slot, first_slot_next, W1_slots, W2_slots):
+    dt = cfg.torch_dtype
+    ne = cfg.E * cfg.d * cfg.f
+    nw = cfg.S_tot * cfg.d * cfg.f
+    per = cfg.E * (3 * cfg.d * cfg.f // cfg.N)
+    _check(lib().symi_adam_to_replicas_active(
+        ctypes.byref(cfg), ctypes.byref(hp), _dev(dW1_class, F32, "dW1_class", 2 * ne),
+        _dev(dW2_class, F32, "dW2_class", ne), _dev(master_w, F32, "master_w", per),
+        _dev(m, F32, "m", per), _dev(v, F32, "v", per),
+        _dev(slot_offsets, I32, "slot_offsets", cfg.S_tot + 1),
+        _dev(first_slot, I32, "first_slot", cfg.E + 1),
+        _dev(first_slot_next, I32, "first_slot_next", cfg.E + 1),
+        _dev(W1_slots, dt, "W1_slots", 2 * nw), _dev(W2_slots, dt, "W2_slots", nw), _stream()),
+        "symi_adam_to_replicas_active")

@@ -46,8 +46,11 @@ __global__ __launch_bounds__(SYMI_ADAM_BLOCK) void adam_to_replicas_kernel(
     const float* __restrict__ dW1, const float* __restrict__ dW2, float* __restrict__ mw,
     float* __restrict__ m, float* __restrict__ v, const int32_t* __restrict__ first_next,
     void* __restrict__ W1s, void* __restrict__ W2s, long long n1, long long n2, long long per,
-    long long lo, AdamScalars hp) {
+    long long lo, AdamScalars hp, const int32_t* __restrict__ slot_offsets,
+    const int32_t* __restrict__ first_slot) {
   const int e = blockIdx.y;
+  // a class that had no rows this iteration: its gradient is zero and is not read
+  const bool has_g = !slot_offsets || slot_offsets[first_slot[e + 1]] > slot_offsets[first_slot[e]];
   const long long groups = per / 8;
   const int q0 = first_next[e], q1 = first_next[e + 1];
   const long long stride = (long long)gridDim.x * SYMI_ADAM_BLOCK;
@@ -65,7 +68,7 @@ __global__ __launch_bounds__(SYMI_ADAM_BLOCK) void adam_to_replicas_kernel(
       const long long so = (long long)e * per + s;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        g[u][h] = ld_stream<NT>(reinterpret_cast<const f32x4*>(gsrc) + h);
+        g[u][h] = has_g ? ld_stream<NT>(reinterpret_cast<const f32x4*>(gsrc) + h) : f32x4{0.f, 0.f, 0.f, 0.f};
         w[u][h] = ld_stream<NT>(reinterpret_cast<const f32x4*>(mw + so) + h);
         mm[u][h] = ld_stream<NT>(reinterpret_cast<const f32x4*>(m + so) + h);
         vv[u][h] = ld_stream<NT>(reinterpret_cast<const f32x4*>(v + so) + h);
@@ -122,17 +125,16 @@ __global__ __launch_bounds__(SYMI_ADAM_BLOCK) void adam_to_replicas_kernel(
 
 using namespace symi;
 
-extern "C" int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp,
-                                     const float* dW1_class, const float* dW2_class,
-                                     float* master_w, float* m, float* v,
-                                     const int32_t* first_slot_next, void* W1_slots,
-                                     void* W2_slots, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_adam_to_replicas")) return rc;
+static int adam_impl(const char* who, const symi_cfg* cfg, const symi_adam* hp,
+                     const float* dW1_class, const float* dW2_class, float* master_w, float* m,
+                     float* v, const int32_t* slot_offsets, const int32_t* first_slot,
+                     const int32_t* first_slot_next, void* W1_slots, void* W2_slots, void* stream) {
+  if (int rc = check_cfg(cfg, who)) return rc;
   SYMI_REQUIRE(hp && dW1_class && dW2_class && master_w && m && v && first_slot_next && W1_slots &&
-                   W2_slots, "symi_adam_to_replicas", "NULL pointer");
-  SYMI_REQUIRE(hp->step >= 1, "symi_adam_to_replicas", "step must be >= 1");
+                   W2_slots, who, "NULL pointer");
+  SYMI_REQUIRE(hp->step >= 1, who, "step must be >= 1");
   SYMI_REQUIRE(hp->beta1 >= 0.f && hp->beta1 < 1.f && hp->beta2 >= 0.f && hp->beta2 < 1.f,
-               "symi_adam_to_replicas", "betas must lie in [0, 1)");
+               who, "betas must lie in [0, 1)");
   const long long n1 = 2LL * cfg->f * cfg->d, n2 = (long long)cfg->d * cfg->f;
   const long long per = (n1 + n2) / cfg->N;
   const long long lo = per * cfg->shard;
@@ -150,10 +152,33 @@ extern "C" int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp,
   hipStream_t st = as_stream(stream);
   if (cfg->dtype == SYMI_BF16)
     SYMI_TIMED(K_ADAM, st, (adam_to_replicas_kernel<true, SYMI_ADAM_NT, SYMI_ADAM_UNROLL><<<grid, SYMI_ADAM_BLOCK, 0, st>>>(
-        dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s)));
+        dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s, slot_offsets, first_slot)));
   else
     SYMI_TIMED(K_ADAM, st, (adam_to_replicas_kernel<false, SYMI_ADAM_NT, SYMI_ADAM_UNROLL><<<grid, SYMI_ADAM_BLOCK, 0, st>>>(
-        dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s)));
-  SYMI_LAUNCH_CHECK("symi_adam_to_replicas");
+        dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s, slot_offsets, first_slot)));
+  SYMI_LAUNCH_CHECK(who);
   return SYMI_OK;
+}
+
+extern "C" int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp,
+                                     const float* dW1_class, const float* dW2_class,
+                                     float* master_w, float* m, float* v,
+                                     const int32_t* first_slot_next, void* W1_slots,
+                                     void* W2_slots, void* stream) {
+  return adam_impl("symi_adam_to_replicas", cfg, hp, dW1_class, dW2_class, master_w, m, v, nullptr,
+                   nullptr, first_slot_next, W1_slots, W2_slots, stream);
+}
+
+extern "C" int symi_adam_to_replicas_active(const symi_cfg* cfg, const symi_adam* hp,
+                                            const float* dW1_class, const float* dW2_class,
+                                            float* master_w, float* m, float* v,
+                                            const int32_t* slot_offsets, const int32_t* first_slot,
+                                            const int32_t* first_slot_next, void* W1_slots,
+                                            void* W2_slots, void* stream) {
+  if (!slot_offsets || !first_slot) {
+    set_error("symi_adam_to_replicas_active: NULL pointer");
+    return SYMI_EINVAL;
+  }
+  return adam_impl("symi_adam_to_replicas_active", cfg, hp, dW1_class, dW2_class, master_w, m, v,
+                   slot_offsets, first_slot, first_slot_next, W1_slots, W2_slots, stream);
 }

@@ -47,6 +47,7 @@ struct GemmParams {
   int d, f;
   const int32_t* class_order;   // weight gradients: classes by decreasing row count
   int per_slot;                 // weight gradients: one output per slot instead of per class
+  int skip_empty;               // weight gradients: a group without rows is not written at all
 };
 
 __device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
@@ -196,6 +197,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   const int n0 = blockIdx.x * (MODE == FWD1 ? BN / 2 : BN);
 
   if (!VARM && K == 0) {
+    if (p.skip_empty) return;   // the caller treats this gradient as zero without reading it
     // a class without rows: its gradient tile is zero; stream it out with one 1 KB row
     // segment per wavefront store
     float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride;
@@ -629,6 +631,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
       kbeg = p.slot_offsets[p.first_slot[group]];
       K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
     }
+    if (K == 0 && p.skip_empty) return;
   }
   const int n0 = blockIdx.x * (MODE == FWD1 ? FB / 2 : FB);
   const float* A = static_cast<const float*>(p.A);
@@ -855,7 +858,7 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
                            const void* UV, const void* H, const int32_t* slot_offsets,
                            const int32_t* first_slot, const void* W1_slots, const void* W2_slots,
                            void* dXp, float* dW1_class, float* dW2_class, void* ws, void* stream,
-                           bool per_slot) {
+                           bool per_slot, bool skip_empty = false) {
   if (int rc = check_cfg(cfg, who)) return rc;
   const long long A = (long long)cfg->T * cfg->k;
   SYMI_REQUIRE(slot_offsets && first_slot && dW1_class && dW2_class && ws, who, "NULL pointer");
@@ -873,6 +876,7 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
   p.first_slot = first_slot;
   p.class_order = order;
   p.per_slot = per_slot ? 1 : 0;
+  p.skip_empty = skip_empty ? 1 : 0;
   p.d = cfg->d;
   p.f = cfg->f;
   SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, first_slot, cfg->S_tot, cfg->E, map, order)));
@@ -935,6 +939,15 @@ extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void*
                                float* dW1_class, float* dW2_class, void* ws, void* stream) {
   return expert_bwd_impl("symi_expert_bwd", cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots,
                          W2_slots, dXp, dW1_class, dW2_class, ws, stream, false);
+}
+
+extern "C" int symi_expert_bwd_active(const symi_cfg* cfg, const void* dYp, const void* Xp,
+                                      const void* UV, const void* H, const int32_t* slot_offsets,
+                                      const int32_t* first_slot, const void* W1_slots,
+                                      const void* W2_slots, void* dXp, float* dW1_class,
+                                      float* dW2_class, void* ws, void* stream) {
+  return expert_bwd_impl("symi_expert_bwd_active", cfg, dYp, Xp, UV, H, slot_offsets, first_slot,
+                         W1_slots, W2_slots, dXp, dW1_class, dW2_class, ws, stream, false, true);
 }
 
 extern "C" int symi_expert_bwd_slots(const symi_cfg* cfg, const void* dYp, const void* Xp,

@@ -33,6 +33,7 @@ class State:
 
     def __init__(self, c: wl.Config, dev="cuda", shard=0, renorm=1, weights=None):
         self.c, self.dev = c, dev
+        self.active_grads = False   # True: the *_active pair (classes without rows are skipped)
         self.cfg = make_cfg(c, shard, renorm)
         dt = self.cfg.torch_dtype
         i32 = dict(dtype=torch.int32, device=dev)
@@ -96,16 +97,22 @@ class State:
     def backward(self, dY, logits):
         s, cfg = self, self.cfg
         symi.symi_combine_bwd(cfg, dY, s.Yp, s.row_of_assign, s.gate, s.dYp, s.dgate)
-        symi.symi_expert_bwd(cfg, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
-                             s.dXp, s.dW1, s.dW2, s.ws)
+        bwd = symi.symi_expert_bwd_active if s.active_grads else symi.symi_expert_bwd
+        bwd(cfg, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
+            s.dXp, s.dW1, s.dW2, s.ws)
         symi.symi_dispatch_bwd(cfg, s.dXp, s.row_of_assign, s.dX)
         symi.symi_route_bwd(cfg, logits, s.idx, s.gate, s.dgate, s.dlogits)
 
     def optimizer(self, adam):
         s, cfg = self, self.cfg
         symi.symi_place(cfg, s.hist, s.counts_next, s.placement_next, s.first_slot_next)
-        symi.symi_adam_to_replicas(cfg, adam, s.dW1, s.dW2, s.master, s.m, s.v, s.first_slot_next,
-                                   s.W1s, s.W2s)
+        if s.active_grads:   # gradients of classes without rows were not written: do not read them
+            symi.symi_adam_to_replicas_active(cfg, adam, s.dW1, s.dW2, s.master, s.m, s.v,
+                                              s.slot_offsets, s.first_slot, s.first_slot_next,
+                                              s.W1s, s.W2s)
+        else:
+            symi.symi_adam_to_replicas(cfg, adam, s.dW1, s.dW2, s.master, s.m, s.v, s.first_slot_next,
+                                       s.W1s, s.W2s)
 
 
 def draw_inputs(c: wl.Config, it=0, dev="cuda"):

@@ -36,6 +36,9 @@ def check_iteration(st: Hn.State, X, logits, dY, hp_kw=None, check_float=True):
     hist_prev = st.hist_prev.cpu().numpy()
     st.place_current()
     st.forward(X, logits)
+    if st.active_grads:      # the *_active pair must neither write nor read these
+        st.dW1.fill_(float("nan"))
+        st.dW2.fill_(float("nan"))
     st.backward(dY, logits)
     adam, hp = Hn.make_adam(**(hp_kw or {}))
     master0, m0, v0 = Hn.npf(st.master), Hn.npf(st.m), Hn.npf(st.v)
@@ -75,8 +78,15 @@ def check_iteration(st: Hn.State, X, logits, dY, hp_kw=None, check_float=True):
     dX, dW1, dW2, dgate = O.moe_backward(Xn, o_idx, o_gate, W1n, W2n, dYn)
     dlog = O.route_backward(zn, o_idx, o_gate, dgate, bool(cfg.renorm))
     check_close("dX", Hn.npf(st.dX), dX, c.dtype, log=log)
-    check_close("dW1", Hn.npf(st.dW1), dW1, c.dtype, group_axis=0, log=log)   # per class
-    check_close("dW2", Hn.npf(st.dW2), dW2, c.dtype, group_axis=0, log=log)
+    gW1, gW2 = Hn.npf(st.dW1), Hn.npf(st.dW2)
+    empty = np.nonzero(o_hist == 0)[0]
+    if st.active_grads:
+        # gradients of classes without rows: left as they were, and zero for the optimizer
+        assert np.isnan(gW1[empty]).all() and np.isnan(gW2[empty]).all()
+        gW1[empty] = 0.0
+        gW2[empty] = 0.0
+    check_close("dW1", gW1, dW1, c.dtype, group_axis=0, log=log)   # per class
+    check_close("dW2", gW2, dW2, c.dtype, group_axis=0, log=log)
     check_close("dgate", Hn.npf(st.dgate), dgate, c.dtype, log=log)
     check_close("dlogits", Hn.npf(st.dlogits), dlog, c.dtype, log=log)
     print("[err] " + " ".join(f"{k}:max={v['max']:.2e},l2={v['l2']:.2e},elem={v['elem']:.2e}"
@@ -85,11 +95,11 @@ def check_iteration(st: Hn.State, X, logits, dY, hp_kw=None, check_float=True):
     dlog_iso = O.route_backward(zn, o_idx, Hn.npf(st.gate), Hn.npf(st.dgate), bool(cfg.renorm))
     assert relerr_elem(Hn.npf(st.dlogits), dlog_iso) <= TOL["f32"]
     # classes without rows have exactly zero gradient
-    for e in np.nonzero(o_hist == 0)[0]:
-        assert not st.dW1[e].any() and not st.dW2[e].any()
+    for e in empty:
+        assert not gW1[e].any() and not gW2[e].any()
     # ---- Adam on the shard, fed the GPU's own gradients (stage isolated)
     W1s_o, W2s_o = W1s0.copy(), W2s0.copy()
-    w2, m2, v2 = O.adam_to_replicas(Hn.npf(st.dW1), Hn.npf(st.dW2), master0, m0, v0, n_place, c.N,
+    w2, m2, v2 = O.adam_to_replicas(gW1, gW2, master0, m0, v0, n_place, c.N,
                                     cfg.shard, hp, c.dtype == "bf16", W1s_o, W2s_o)
     assert relerr_elem(Hn.npf(st.master), w2) <= TOL["adam"]
     assert relerr_elem(Hn.npf(st.m), m2) <= TOL["adam"]
