@@ -203,10 +203,7 @@ def run_gpu(args):
         st.forward(X, logits)
         st.backward(dY, logits)
         st.optimizer(adam)
-        # the placement computed in this step is the one the next step dispatches with
-        st.counts, st.counts_next = st.counts_next, st.counts
-        st.first_slot, st.first_slot_next = st.first_slot_next, st.first_slot
-        st.placement, st.placement_next = st.placement_next, st.placement
+        st.advance()   # the placement computed in this step is the one the next step dispatches with
 
     def timed(n_steps, first, events):
         """n_steps steps, optionally with a HIP event pair around every launch; returns ms per
@@ -229,13 +226,45 @@ def run_gpu(args):
         symi.symi_timing_reset()
         return (t1 - t0) * 1e3 / n_steps, got
 
+    def timed_graphs(n_steps, first):
+        """The same n_steps steps replayed from HIP graphs: one graph per distinct step (the
+        inputs cycle with period `iters`, the current/next placement buffers with period 2)."""
+        import math
+        period = math.lcm(2, iters)
+        graphs = []
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for j in range(min(period, n_steps)):
+                g = torch.cuda.CUDAGraph()
+                g.capture_begin()
+                step(first + j)
+                g.capture_end()
+                graphs.append(g)
+            if len(graphs) % 2:       # the captures swapped the buffer roles an odd number of times
+                st.advance()
+            Hn.sync()
+            t0 = time.perf_counter()
+            for j in range(n_steps):
+                graphs[j % period].replay()
+            Hn.sync()
+            t1 = time.perf_counter()
+        torch.cuda.current_stream().wait_stream(side)
+        if n_steps % 2:               # the eager steps that follow start where the replays ended
+            st.advance()
+        del graphs
+        return (t1 - t0) * 1e3 / n_steps
+
     symi.symi_set_overlap(not args.no_overlap)
     for i in range(args.warmup):
         step(i)
     # the timed region: the library as it ships, nothing but the K steps between two
     # synchronisations (no events: a pair around each of the ~20 launches of a step costs 6 % on
     # c2; the backward's two chains of products may share the chip on two streams)
-    ms_per_step, _ = timed(args.steps, args.warmup, False)
+    if args.graph:
+        ms_per_step = timed_graphs(args.steps, args.warmup)
+    else:
+        ms_per_step, _ = timed(args.steps, args.warmup, False)
     # per-kernel durations and the roofline come from the same steps run again with HIP events
     # around every launch and one kernel at a time on the stream, which is also what the
     # committed rocprofv3 summary shows
@@ -306,6 +335,7 @@ def run_gpu(args):
         "gpu_kernel_ms_per_step": round(gpu_ms, 4),
         "ms_per_step_second_pass": round(ms_serial, 4),
         "kernel_table": "second pass of the same steps: HIP events around every launch, symi_set_overlap(0)",
+        "launch": "HIP graph replay" if args.graph else "host launches",
         "nonempty_slots_mean": round(mean_nonempty, 2),
         "classes_with_tokens_mean": round(mean_active, 2),
         "kernels": kernels,
@@ -377,6 +407,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep every kernel on one stream also in the timed region (symi_set_overlap(0))")
+    ap.add_argument("--graph", action="store_true",
+                    help="timed region replays the steps from captured HIP graphs instead of launching "
+                         "every kernel from the host")
     ap.add_argument("--dense-grads", action="store_true",
                     help="symi_expert_bwd / symi_adam_to_replicas (zero gradients of classes without "
                          "tokens written and read back) instead of the *_active pair")

@@ -197,6 +197,13 @@ int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* Wr, const fl
  * batches); symi_set_overlap(0) keeps every kernel on `stream` itself, (1) is the default. */
 int symi_set_overlap(int on);
 
+/* symi_expert_fwd / symi_expert_bwd cut the reduction of the last round's tiles of the two
+ * narrow products (Yp = H W2^T, dXp = dUV W1) into slices when that round would leave at
+ * least half the compute units idle, and add the slices up in a fixed order (same bits on
+ * every run; not the bits of the uncut reduction).  symi_set_slicing(0) turns that off,
+ * (1) is the default. */
+int symi_set_slicing(int on);
+
 /* The same two calls for a batch that leaves many classes without tokens.  A rank of the
  * paper only ever forms gradients for the classes it hosts (Sec. 4.1; Algorithm 2 collects a
  * shard from a hosting rank), and a class no token chose contributes a zero gradient to the

@@ -19,7 +19,7 @@ EXPORTS = [
     "symi_dispatch_capacity", "symi_dispatch_bwd", "symi_expert_fwd",
     "symi_expert_bwd", "symi_combine", "symi_combine_bwd", "symi_adam_to_replicas",
     "symi_timing_enable", "symi_timing_reset", "symi_timing_read", "symi_kernel_count",
-    "symi_kernel_name", "symi_expert_bwd_slots", "symi_expert_bwd_active", "symi_adam_to_replicas_active", "symi_set_overlap", "symi_replica_allreduce", "symi_router_fwd", "symi_router_bwd",
+    "symi_kernel_name", "symi_expert_bwd_slots", "symi_expert_bwd_active", "symi_adam_to_replicas_active", "symi_set_overlap", "symi_set_slicing", "symi_replica_allreduce", "symi_router_fwd", "symi_router_bwd",
     "symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost",
 ]
 
@@ -110,7 +110,7 @@ def lib():
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
         L.symi_rank_group.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.symi_comm_cost.argtypes = [ctypes.POINTER(SymiCostIn), ctypes.POINTER(SymiCostOut)]
-        for name in ("symi_expert_bwd_slots", "symi_set_overlap", "symi_replica_allreduce", "symi_router_fwd", "symi_router_bwd",
+        for name in ("symi_expert_bwd_slots", "symi_set_overlap", "symi_set_slicing", "symi_replica_allreduce", "symi_router_fwd", "symi_router_bwd",
     "symi_grad_source", "symi_collect_grads", "symi_rank_group", "symi_comm_cost"):
             getattr(L, name).restype = ctypes.c_int
         L.symi_workspace_bytes.argtypes = [cfgp]
@@ -119,6 +119,8 @@ def lib():
         L.symi_last_error.restype = ctypes.c_char_p
         L.symi_set_overlap.argtypes = [ctypes.c_int]
         L.symi_set_overlap.restype = ctypes.c_int
+        L.symi_set_slicing.argtypes = [ctypes.c_int]
+        L.symi_set_slicing.restype = ctypes.c_int
         L.symi_timing_enable.argtypes = [ctypes.c_int]
         L.symi_timing_reset.argtypes = []
         L.symi_timing_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double),
@@ -359,6 +361,10 @@ def symi_expert_bwd_slots(cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slot
 
 def symi_set_overlap(on):
     lib().symi_set_overlap(1 if on else 0)
+
+
+def symi_set_slicing(on):
+    lib().symi_set_slicing(1 if on else 0)
 
 
 def symi_replica_allreduce(cfg, first_slot, scale, dW1_slot, dW2_slot):

@@ -64,6 +64,8 @@ WsLayout ws_layout(const symi_cfg* c) {
   off += align_up((size_t)c->E * sizeof(int32_t), 256);
   L.duv = off;
   off += align_up(A * 2 * c->f * w, 256);
+  L.split_part = off;
+  off += c->dtype == SYMI_BF16 ? (size_t)SPLIT_CUS * SPLIT_TILE_BYTES : 0;
   L.router_partial = off;
   off += align_up(((size_t)c->T + 511) / 512 * c->E * c->d * sizeof(float), 256);
   L.router_bias_partial = off;
@@ -81,7 +83,7 @@ static const char* const g_names[K_COUNT] = {
     "fill_i32", "route", "route_bwd", "place", "chunk_count", "chunk_scan", "chunk_rank",
     "gather_rows", "tile_map", "gemm_fwd1", "gemm_fwd2", "gemm_bwd_dh", "gemm_bwd_dx",
     "gemm_wgrad2", "gemm_wgrad1", "combine", "combine_bwd", "dispatch_bwd", "adam_to_replicas",
-    "replica_allreduce", "router_fwd", "router_dx", "router_dw"};
+    "replica_allreduce", "router_fwd", "router_dx", "router_dw", "slice_sum"};
 
 void timing_begin(int kid, hipStream_t st) {
   hipEvent_t e;

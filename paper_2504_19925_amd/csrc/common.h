@@ -16,7 +16,7 @@ void launch_fill_i32(int32_t* p, int n, int32_t val, hipStream_t st);
 enum KernelId {
   K_FILL = 0, K_ROUTE, K_ROUTE_BWD, K_PLACE, K_CHUNK_COUNT, K_CHUNK_SCAN, K_CHUNK_RANK, K_GATHER,
   K_TILE_MAP, K_GEMM_FWD1, K_GEMM_FWD2, K_GEMM_BWD_DH, K_GEMM_BWD_DX, K_GEMM_WGRAD2, K_GEMM_WGRAD1,
-  K_COMBINE, K_COMBINE_BWD, K_DISPATCH_BWD, K_ADAM, K_REPLICA_AR, K_ROUTER_FWD, K_ROUTER_DX, K_ROUTER_DW, K_COUNT
+  K_COMBINE, K_COMBINE_BWD, K_DISPATCH_BWD, K_ADAM, K_REPLICA_AR, K_ROUTER_FWD, K_ROUTER_DX, K_ROUTER_DW, K_SLICE_SUM, K_COUNT
 };
 extern bool g_timing;
 void timing_begin(int kid, hipStream_t st);
@@ -76,6 +76,7 @@ struct WsLayout {
   size_t tile_map;     // expert fwd/bwd: m-tile table, see gemm.hip
   size_t class_order;  // expert bwd: classes by decreasing row count
   size_t duv;          // expert bwd: dUV [A,2f] in the activation dtype
+  size_t split_part;   // expert fwd/bwd: partial tiles of sliced reductions, see gemm.hip
   size_t router_partial;  // router bwd (bf16): partial weight gradients [chunks,E,d] f32
   size_t router_bias_partial;  // router bwd: partial bias gradients [chunks,E] f32
   size_t total;
@@ -84,5 +85,8 @@ WsLayout ws_layout(const symi_cfg* cfg);
 
 constexpr int DISPATCH_CHUNK = 1024;  // assignments ranked by one workgroup
 constexpr int GEMM_BM = 256;          // rows of one m-tile in the tile map
+// Sliced reductions (gemm.hip): at most SPLIT_CUS partial tiles of 256 x 256 fp32 = 256 KB each.
+constexpr int SPLIT_CUS = 256;        // compute units the slicing fills (at most)
+constexpr size_t SPLIT_TILE_BYTES = 256 * 256 * sizeof(float);
 
 }  // namespace symi

@@ -18,6 +18,7 @@
 // The MFMA is issued with the weight tile as its first operand, so a lane ends up with 4
 // consecutive output columns of one output row; the epilogue turns the blocks around through
 // LDS so that stores cover whole cache lines.
+#include <algorithm>
 #include <type_traits>
 
 #include "common.h"
@@ -48,6 +49,8 @@ struct GemmParams {
   const int32_t* class_order;   // weight gradients: classes by decreasing row count
   int per_slot;                 // weight gradients: one output per slot instead of per class
   int skip_empty;               // weight gradients: a group without rows is not written at all
+  float* partials;              // partial tiles of sliced reductions (nullptr: never slice)
+  int cus;                      // compute units a round of tiles is spread over
 };
 
 __device__ __forceinline__ float silu_f(float u) { return u / (1.f + expf(-u)); }
@@ -154,6 +157,27 @@ __device__ __forceinline__ bf16x8 lds_read_tr(unsigned addr) {
   return u.v;
 }
 
+// Reduction slices of the narrow variable-row products (FWD2, BWD_DX).  Their tiles run in
+// launch order, one workgroup per tile, in rounds of `cus`.  If the last round would leave at
+// least half the chip idle (config c2: 300 tiles, a second round of 44), each of its tiles is
+// cut into `sl` slices of at least 16 reduction steps, as many as fill the round (at most 8);
+// a slice leaves its accumulators as a plain fp32 tile in a partial slot and slice_sum_kernel,
+// launched behind the product, adds them up in slice order.  full = tiles that stay whole.
+// (Letting the slice that finishes last add up the partials inside the product was measured
+// slower than no slicing at all: device-scope fences write back / invalidate the whole L2 of
+// an XCD under the other tiles' feet, and without fences one workgroup reads a megabyte of
+// uncached partials at some 16 GB/s.  Slicing the weight gradients of very popular classes the
+// same way cost more in partial traffic than the shorter tail returned.)
+__device__ __forceinline__ void tail_slices(int n_tiles, int cus, int K, int& full, int& sl) {
+  full = n_tiles;
+  sl = 1;
+  const int rem = n_tiles % cus;
+  if (rem > 0 && 2 * rem <= cus) {
+    const int s = min(min(cus / rem, 8), (K + BK - 1) / BK / 16);
+    if (s >= 2) { sl = s; full = n_tiles - rem; }
+  }
+}
+
 template <int MODE>
 __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   // [left stage 0 | left stage 1 | right stage 0 | right stage 1], 32 KB each: the two
@@ -170,14 +194,37 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   constexpr bool A_KC = VARM;                       // left operand reduction-contiguous
   constexpr bool B_KC = MODE == FWD1 || MODE == FWD2;
 
-  int row0, row1, group, kbeg = 0, K;
+  int row0, row1, group, kbeg = 0, K, bx = blockIdx.x;
+  // this workgroup reduces slice zsl of nsl, starting at reduction index kofs; if nsl > 1 its
+  // accumulators go to partial slot pslot
+  int nsl = 1, zsl = 0, kofs = 0, pslot = 0;
   if (VARM) {
-    const int mt = blockIdx.y;
-    if (mt >= p.tile_map[0]) return;
+    // tiles in launch order (column index fastest); the last round's tiles may be sliced
+    const int ntx = gridDim.x;
+    const int n_tiles = p.tile_map[0] * ntx;
+    const int b = blockIdx.y * ntx + blockIdx.x;
+    int full = n_tiles, sl = 1;
+    if ((MODE == FWD2 || MODE == BWD_DX) && p.partials) tail_slices(n_tiles, p.cus, p.K, full, sl);
+    int tile = b;
+    if (b >= full) {
+      tile = full + (b - full) / sl;
+      zsl = (b - full) % sl;
+      nsl = sl;
+    }
+    if (tile >= n_tiles) return;
+    const int mt = tile / ntx;
+    bx = tile - mt * ntx;
     row0 = p.tile_map[4 + 4 * mt];
     row1 = p.tile_map[4 + 4 * mt + 1];
     group = p.tile_map[4 + 4 * mt + 2];
     K = p.K;
+    if (nsl > 1) {
+      const int nk_all = (p.K + BK - 1) / BK;
+      const int len = ((nk_all + nsl - 1) / nsl + 1) / 2 * 2 * BK;   // whole pairs of steps
+      kofs = zsl * len;
+      K = max(0, min(len, p.K - kofs));
+      pslot = (tile - full) * nsl + zsl;
+    }
   } else {
     // classes in order of decreasing row count: the long reductions start first and the
     // short (or empty, store-only) tiles fill in behind them
@@ -194,7 +241,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   }
   // FWD1: a tile holds 128 hidden units; every 64 tile columns are 32 gate columns
   // followed by the 32 up columns of the same hidden units.
-  const int n0 = blockIdx.x * (MODE == FWD1 ? BN / 2 : BN);
+  const int n0 = bx * (MODE == FWD1 ? BN / 2 : BN);
 
   if (!VARM && K == 0) {
     if (p.skip_empty) return;   // the caller treats this gradient as zero without reading it
@@ -239,17 +286,17 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   const uint16_t* b_base;
   int a_lim, b_lim;         // KC: last valid tile row; KS: number of valid columns
   if (A_KC) {
-    a_base = A + (long long)row0 * lda;
+    a_base = A + (long long)row0 * lda + kofs;
     a_lim = row1 - row0 - 1;
   } else {
     a_base = A + (long long)kbeg * lda + row0;
     a_lim = row1 - row0;
   }
   if (B_KC) {
-    b_base = MODE == FWD1 ? B : B + (long long)n0 * ldb;
+    b_base = (MODE == FWD1 ? B : B + (long long)n0 * ldb) + kofs;
     b_lim = MODE == FWD1 ? p.f - 1 : p.N - n0 - 1;
   } else {
-    b_base = (VARM ? B : B + (long long)kbeg * ldb) + n0;
+    b_base = (VARM ? B + (long long)kofs * ldb : B + (long long)kbeg * ldb) + n0;
     b_lim = p.N - n0;
   }
   // LDS destination of instruction j (wave-uniform): both layouts advance 1 KB per j
@@ -451,6 +498,8 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   constexpr int LDH = 72;    // u / v / h rows of 64 hidden units + pad (144 B)
   constexpr int LDF = 132;   // fp32 row of 128 columns + pad (528 B)
   uint4 uvu[2][8], uvv[2][8];   // BWD_DH: saved u, v of the current and the next 32-row block
+  // a slice stores its accumulators the way a weight gradient is stored: fp32, pitch 256
+  const bool to_partial = (MODE == FWD2 || MODE == BWD_DX) && nsl > 1;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int rbase = row0 + wm * 128 + i * 32;   // first output row of this block
@@ -555,7 +604,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
           *reinterpret_cast<uint4*>(Co + o + p.f) = make_uint4(dv[0], dv[1], dv[2], dv[3]);
         }
       }
-    } else if (MODE == FWD2 || MODE == BWD_DX) {
+    } else if ((MODE == FWD2 || MODE == BWD_DX) && !to_partial) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -582,19 +631,59 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
           *reinterpret_cast<float4*>(sf + r32 * LDF + 32 * j + 8 * g + 4 * hw) =
               make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
       __builtin_amdgcn_s_waitcnt(0xC07F);
-      float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride;
-      const int col = n0 + wn * 128 + (lane & 31) * 4;
+      if (VARM) {   // a slice's partial tile
+        float* Co = p.partials + (size_t)pslot * (BM * BN) + (wm * 128 + i * 32) * BN + wn * 128 + (lane & 31) * 4;
 #pragma unroll
-      for (int it = 0; it < 16; ++it) {
-        const int rr = it * 2 + (lane >> 5);
-        const int row = rbase + rr;
-        const float4 x = *reinterpret_cast<const float4*>(sf + rr * LDF + (lane & 31) * 4);
-        if (row < row1 && col < p.N) *reinterpret_cast<float4*>(Co + (long long)row * p.N + col) = x;
+        for (int it = 0; it < 16; ++it) {
+          const int rr = it * 2 + (lane >> 5);
+          *reinterpret_cast<float4*>(Co + rr * BN) = *reinterpret_cast<const float4*>(sf + rr * LDF + (lane & 31) * 4);
+        }
+      } else {
+        float* Co = static_cast<float*>(p.C) + (long long)group * p.c_group_stride;
+        const int col = n0 + wn * 128 + (lane & 31) * 4;
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+          const int rr = it * 2 + (lane >> 5);
+          const int row = rbase + rr;
+          const float4 x = *reinterpret_cast<const float4*>(sf + rr * LDF + (lane & 31) * 4);
+          if (row < row1 && col < p.N) *reinterpret_cast<float4*>(Co + (long long)row * p.N + col) = x;
+        }
       }
     }
     // the next block reuses the staging area: its writes must not pass these reads
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// ---------------------------------------------------------------- sum of reduction slices
+// Runs behind FWD2 / BWD_DX (same stream): adds the partial tiles of every sliced tile in slice
+// order and writes the bf16 rows of the product.  Workgroup = 16 rows of a tile, a lane four
+// consecutive columns of four rows.  Returns at once if the product's tail was not sliced.
+__global__ __launch_bounds__(256) void slice_sum_kernel(GemmParams p, int ntx) {
+  const int tid = threadIdx.x;
+  const int n_tiles = p.tile_map[0] * ntx;
+  int full, sl;
+  tail_slices(n_tiles, p.cus, p.K, full, sl);
+  const int tile = full + blockIdx.y;
+  if (sl < 2 || tile >= n_tiles) return;
+  const int mt = tile / ntx;
+  const int row0 = p.tile_map[4 + 4 * mt], row1 = p.tile_map[4 + 4 * mt + 1];
+  const int n0 = (tile - mt * ntx) * BN;
+  const float* part = p.partials + (size_t)blockIdx.y * sl * (BM * BN);
+  const int c = (tid & 63) * 4;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int r = blockIdx.x * 16 + it * 4 + (tid >> 6);
+    const int row = row0 + r, col = n0 + c;
+    if (row >= row1 || col >= p.N) continue;
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z = 0; z < sl; ++z) {
+      const float4 x = *reinterpret_cast<const float4*>(part + (size_t)z * (BM * BN) + r * BN + c);
+      sum.x += x.x; sum.y += x.y; sum.z += x.z; sum.w += x.w;
+    }
+    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C) + (long long)row * p.N + col) =
+        make_uint2(pack_bf16x2(sum.x, sum.y), pack_bf16x2(sum.z, sum.w));
   }
 }
 
@@ -762,13 +851,40 @@ static void launch_gemm(const symi_cfg* cfg, const GemmParams& p, int n_cols, in
                         hipStream_t st) {
   if (cfg->dtype == SYMI_BF16) {
     const int bn = MODE == FWD1 ? BN / 2 : BN;
-    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? max_mtiles : cdiv(p.M, BM), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
+    const int ntx = cdiv(n_cols, bn);
+    // FWD2, BWD_DX: room for the slices of the last round's tiles (at most cus workgroups more)
+    const bool may_slice = (MODE == FWD2 || MODE == BWD_DX) && p.partials && cdiv(p.K, BK) / 16 >= 2;
+    const int extra = may_slice ? cdiv(p.cus, ntx) : 0;
+    dim3 grid(ntx, MODE <= BWD_DX ? max_mtiles + extra : cdiv(p.M, BM), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
     SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_bf16_kernel<MODE><<<grid, GT, 0, st>>>(p)));
+    if (may_slice)   // the sliced round holds at most cus / 2 tiles
+      SYMI_TIMED(K_SLICE_SUM, st, (slice_sum_kernel<<<dim3(BM / 16, p.cus / 2), 256, 0, st>>>(p, ntx)));
   } else {
     const int bn = MODE == FWD1 ? FB / 2 : FB;
     dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 4 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
     SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_f32_kernel<MODE><<<grid, 256, 0, st>>>(p)));
   }
+}
+
+// compute units of the current device
+static int device_cus() {
+  static int cus[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    cus[dev] = n;
+  }
+  return cus[dev];
+}
+
+// where sliced reductions keep their partial tiles (bf16 configurations only)
+static bool g_slicing = true;
+static void set_split(const symi_cfg* cfg, void* ws, const WsLayout& L, GemmParams& p) {
+  p.cus = std::min(device_cus(), SPLIT_CUS);
+  p.partials = g_slicing && cfg->dtype == SYMI_BF16
+                   ? reinterpret_cast<float*>(static_cast<char*>(ws) + L.split_part) : nullptr;
 }
 
 }  // namespace symi
@@ -791,6 +907,7 @@ extern "C" int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_
 
   GemmParams p = {};
   p.tile_map = map;
+  set_split(cfg, ws, L, p);
   p.d = cfg->d;
   p.f = cfg->f;
   // u|v = Xp W1^T, h = silu(u)*v
@@ -805,19 +922,6 @@ extern "C" int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_
   launch_gemm<FWD2>(cfg, p, cfg->d, max_mtiles, st);
   SYMI_LAUNCH_CHECK("symi_expert_fwd");
   return SYMI_OK;
-}
-
-// compute units of the current device
-static int device_cus() {
-  static int cus[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cus[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-    cus[dev] = n;
-  }
-  return cus[dev];
 }
 
 // The backward's five products form two chains that only meet at du|dv:
@@ -877,6 +981,7 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
   p.class_order = order;
   p.per_slot = per_slot ? 1 : 0;
   p.skip_empty = skip_empty ? 1 : 0;
+  set_split(cfg, ws, L, p);
   p.d = cfg->d;
   p.f = cfg->f;
   SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, first_slot, cfg->S_tot, cfg->E, map, order)));
@@ -925,6 +1030,11 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
     }
   }
   SYMI_LAUNCH_CHECK(who);
+  return SYMI_OK;
+}
+
+extern "C" int symi_set_slicing(int on) {
+  g_slicing = on != 0;
   return SYMI_OK;
 }
 

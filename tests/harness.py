@@ -114,6 +114,14 @@ class State:
             symi.symi_adam_to_replicas(cfg, adam, s.dW1, s.dW2, s.master, s.m, s.v, s.first_slot_next,
                                        s.W1s, s.W2s)
 
+    def advance(self):
+        """The placement computed by optimizer() becomes the one the next iteration dispatches
+        with (the two sets of placement buffers swap roles)."""
+        s = self
+        s.counts, s.counts_next = s.counts_next, s.counts
+        s.first_slot, s.first_slot_next = s.first_slot_next, s.first_slot
+        s.placement, s.placement_next = s.placement_next, s.placement
+
 
 def draw_inputs(c: wl.Config, it=0, dev="cuda"):
     X = wl.make_tokens(c, it, dev)

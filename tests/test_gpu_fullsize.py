@@ -122,3 +122,64 @@ def test_fullsize_sampled_parity(name):
         slots = torch.cat([st.W1s[qs].reshape(-1, n1), st.W2s[qs].reshape(-1, c.d * c.f)], 1)[:, lo:lo + per]
         assert torch.equal(slots, st.master[pl[qs]].to(st.W1s.dtype))
     print("[fullsize] adam + slots ok", flush=True)
+
+
+@pytest.mark.timeout(600)
+def test_sliced_tail_tiles_against_the_oracle():
+    """On c2 the two narrow products (Yp, dXp) are 300 tiles: the last round's 44 tiles have
+    their reduction cut into slices that a second kernel adds up.  Tokens whose rows lie in
+    those tiles are checked against the oracle; the sliced result is reproducible bit for bit
+    and within one bf16 rounding of the unsliced one (up to reordering noise where a sum cancels)."""
+    import paper_2504_19925_amd as symi
+    c = wl.get_config("c2")
+    st = Hn.State(c, shard=0)
+    X, logits, dY = Hn.draw_inputs(c, 0)
+    st.place_current()
+    st.forward(X, logits)
+    st.backward(dY, logits)
+    Hn.sync()
+    # the library's slicing rule, restated on the host
+    so = st.slot_offsets.cpu().numpy()
+    mt_rows = [(r, min(r + 256, so[q + 1])) for q in range(c.S_tot) for r in range(so[q], so[q + 1], 256)]
+    cus = min(torch.cuda.get_device_properties(0).multi_processor_count, 256)
+    ntx = -(-c.d // 256)
+    n_tiles = len(mt_rows) * ntx
+    rem = n_tiles % cus
+    assert 0 < rem <= cus // 2, (n_tiles, cus)
+    for K in (c.f, 2 * c.f):
+        assert min(cus // rem, 8, -(-K // 64) // 16) >= 2
+    first_sliced_mt = -(-(n_tiles - rem) // ntx)        # m-tiles all of whose tiles are sliced
+    rows = np.concatenate([np.arange(a, b) for a, b in mt_rows[first_sliced_mt:]])
+    assert len(rows) > 0
+    rng = np.random.default_rng(99)
+    pick = rng.choice(rows, size=min(40, len(rows)), replace=False)
+    toks = np.unique(st.assign_of_row.cpu().numpy()[pick] // c.k)
+    tt = torch.tensor(toks, device="cuda")
+    o_idx, o_gate, _ = O.route(Hn.npf(logits[tt]), c.k, True)
+    W1L, W2L = Hn.LazyWeights(st.W1c), Hn.LazyWeights(st.W2c)
+    Ys = O.moe_forward(Hn.npf(X[tt]), o_idx, o_gate, W1L, W2L)
+    dXs, _, _, _ = O.moe_backward(Hn.npf(X[tt]), o_idx, o_gate, W1L, W2L, Hn.npf(dY[tt]))
+    check_close("Y", Hn.npf(st.Y[tt]), Ys, c.dtype)
+    check_close("dX", Hn.npf(st.dX[tt]), dXs, c.dtype)
+    # reproducible, and one rounding away from the uncut reduction at most
+    Yp1, dXp1 = st.Yp.clone(), st.dXp.clone()
+    st.forward(X, logits)
+    st.backward(dY, logits)
+    Hn.sync()
+    assert torch.equal(st.Yp, Yp1) and torch.equal(st.dXp, dXp1)
+    symi.symi_set_slicing(False)
+    try:
+        st.forward(X, logits)
+        st.backward(dY, logits)
+        Hn.sync()
+    finally:
+        symi.symi_set_slicing(True)
+    rr = torch.tensor(rows, device="cuda")
+    other = torch.zeros(c.A, dtype=torch.bool, device="cuda")
+    other[:mt_rows[(n_tiles - rem) // ntx][0]] = True      # rows of m-tiles with no sliced tile
+    assert torch.equal(st.Yp[other], Yp1[other]) and torch.equal(st.dXp[other], dXp1[other])
+    for a, b in ((st.Yp[rr], Yp1[rr]), (st.dXp[rr], dXp1[rr])):
+        a, b = a.float(), b.float()
+        # one bf16 rounding of the value, or (where the sum cancels) of the fp32 reordering noise
+        assert ((a - b).abs() <= 2.0 ** -7 * b.abs() + 2.0 ** -12 * b.abs().max()).all()
+        assert not torch.equal(a, b)        # the slices really were summed in another order

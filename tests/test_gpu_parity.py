@@ -308,3 +308,56 @@ def test_forward_backward_under_graph_capture():
         Hn.sync()
         for t, w in zip(outs, want):
             assert torch.equal(t, w), f"replay {rep}"
+
+
+def test_whole_steps_replayed_from_graphs_equal_eager_steps():
+    """Layer, backward, placement and optimizer of consecutive iterations captured as one HIP
+    graph per distinct step (inputs of period 2, placement buffers of period 2) and replayed:
+    the optimizer state and the slots end up bit for bit where eager launches put them."""
+    c = _small("c2")
+    weights = wl.make_class_weights(c, "cuda")
+    inputs = [Hn.draw_inputs(c, it) for it in range(2)]
+    adam, _ = Hn.make_adam(step=2)
+
+    def make():
+        st = Hn.State(c, shard=1, weights=weights)
+        st.active_grads = True
+        st.place_current()
+        return st
+
+    def step(st, i):
+        X, logits, dY = inputs[i % 2]
+        st.forward(X, logits)
+        st.backward(dY, logits)
+        st.optimizer(adam)
+        st.advance()
+
+    a, b = make(), make()
+    for st in (a, b):
+        step(st, 0)                   # eager: also creates the helper stream outside any capture
+    Hn.sync()
+    for i in range(1, 6):
+        step(a, i)
+    Hn.sync()
+    graphs = []
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    scratch = torch.empty(1 << 20, device="cuda")
+    with torch.cuda.stream(side):
+        for i in (1, 2):
+            g = torch.cuda.CUDAGraph()
+            g.capture_begin()
+            step(b, i)
+            g.capture_end()
+            graphs.append(g)
+        Hn.sync()
+        for i in range(1, 6):
+            graphs[(i - 1) % 2].replay()
+            scratch.normal_()         # eager work and a synchronisation between the replays
+            Hn.sync()
+    torch.cuda.current_stream().wait_stream(side)
+    b.advance()                       # five replays: an odd number of role swaps on the device side
+    Hn.sync()
+    for name in ("master", "m", "v", "W1s", "W2s", "Y", "dX", "dlogits", "hist", "placement",
+                 "first_slot", "slot_offsets"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
