@@ -361,3 +361,33 @@ def test_whole_steps_replayed_from_graphs_equal_eager_steps():
     for name in ("master", "m", "v", "W1s", "W2s", "Y", "dX", "dlogits", "hist", "placement",
                  "first_slot", "slot_offsets"):
         assert torch.equal(getattr(a, name), getattr(b, name)), name
+
+
+def test_sliced_reductions_with_ragged_lengths():
+    """A few m-tiles and long reductions: the two narrow products (Yp over f, dXp over 2f) have
+    their tiles' reductions cut into slices (2 and 4 here on a 256-CU part), the last slice
+    ending in a partial 64-deep step; checked element by element against the oracle, and
+    equal, up to the order of the fp32 sums, to the uncut products."""
+    c = wl.scaled(wl.get_config("c2"), E=8, S_tot=16, N=4, d=512, f=2056, T=1100, iters=1)
+    print(f"[sliced] {c}", flush=True)
+    st = Hn.State(c, shard=2)
+    X, logits, dY = Hn.draw_inputs(c, 0)
+    check_iteration(st, X, logits, dY)
+    st.forward(X, logits)            # again: the optimizer has rewritten the slots meanwhile
+    st.backward(dY, logits)
+    Hn.sync()
+    Yp, dXp = st.Yp.clone(), st.dXp.clone()
+    symi.symi_set_slicing(False)
+    try:
+        st.forward(X, logits)
+        st.backward(dY, logits)
+        Hn.sync()
+    finally:
+        symi.symi_set_slicing(True)
+    for a, b in ((st.Yp, Yp), (st.dXp, dXp)):
+        a, b = a.float(), b.float()
+        assert ((a - b).abs() <= 2.0 ** -7 * b.abs() + 2.0 ** -12 * b.abs().max()).all()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    n_tiles = int(((st.slot_offsets[1:] - st.slot_offsets[:-1] + 255) // 256).sum()) * (c.d // 256)
+    if 0 < n_tiles % min(cus, 256) <= min(cus, 256) // 2:
+        assert not torch.equal(st.Yp, Yp) and not torch.equal(st.dXp, dXp)   # slices were used
