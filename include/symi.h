@@ -9,6 +9,8 @@
  *   optimizer  symi_place (next placement, Algorithm 1) -> symi_adam_to_replicas
  *   optional   symi_router_fwd before symi_route, symi_router_bwd after symi_route_bwd;
  *              symi_expert_bwd_slots + symi_replica_allreduce instead of symi_expert_bwd;
+ *              symi_expert_bwd_active + symi_adam_to_replicas_active instead of the plain
+ *              pair when many classes get no tokens;
  *              host helpers for the multi-rank plan at the end of this file
  *
  * Conventions
@@ -19,6 +21,7 @@
  *     allocates no memory and never synchronises with the host inside these calls (the
  *     only objects it creates are one helper stream and three events per device, at the
  *     first symi_expert_bwd call; see symi_set_overlap).  Calls are not thread-safe.
+ *     Every call may be captured into a HIP graph (no memsets, no host synchronisation).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - `cfg` and `hp` are HOST pointers, read during the call only.
  *   - Activations and slot weights are fp32 or bf16 according to cfg->dtype; routing
