@@ -21,7 +21,8 @@
  *     allocates no memory and never synchronises with the host inside these calls (the
  *     only objects it creates are one helper stream and three events per device, at the
  *     first symi_expert_bwd call; see symi_set_overlap).  Calls are not thread-safe.
- *     Every call may be captured into a HIP graph (no memsets, no host synchronisation).
+ *     The device calls can be captured into a HIP graph (no memsets, no host synchronisation);
+ *     call symi_expert_bwd once eagerly first, so that its helper stream exists.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - `cfg` and `hp` are HOST pointers, read during the call only.
  *   - Activations and slot weights are fp32 or bf16 according to cfg->dtype; routing
