@@ -13,7 +13,9 @@
 //   WGRAD1 dW1_e = dUV^T * Xp      over all rows of class e
 // The first four have a variable number of rows per group (one group per slot); a small
 // kernel turns slot_offsets into a table of 256-row m-tiles so that no workgroup spans
-// two slots.  The last two have a variable reduction length (the rows of a class).
+// two slots.  The last two have a variable reduction length (the rows of a class).  The two
+// narrow products (FWD2, BWD_DX) may cut the reduction of their last round's tiles into slices
+// that a second small kernel adds up (tail_slices, slice_sum_kernel).
 //
 // The MFMA is issued with the weight tile as its first operand, so a lane ends up with 4
 // consecutive output columns of one output row; the epilogue turns the blocks around through
