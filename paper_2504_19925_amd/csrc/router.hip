@@ -25,7 +25,7 @@ constexpr int RLD = RK + 8;    // padded LDS row of a [row][k] tile (elements; 1
 constexpr int RLS = RT + 32;   // padded LDS row of a [k][row] tile (320 B: four k-rows cover 64 banks)
 constexpr int RTILE = RT * RLD > RK * RLS ? RT * RLD : RK * RLS;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short rshortx4;
-constexpr int RCHUNK = 512;    // tokens per partial weight gradient
+constexpr int RCHUNK = 512;    // tokens per partial weight gradient, at least
 
 enum { R_FWD = 0, R_DX = 1, R_DW = 2 };
 
@@ -38,6 +38,7 @@ struct RouterParams {
   void* dX;             // [T,d] accumulated into
   float* partial;       // [nchunk,E,d]
   int T, E, d;
+  int chunk;            // tokens per partial weight gradient
 };
 
 __device__ __forceinline__ uint4 pack8(const float (&v)[8]) {
@@ -106,8 +107,8 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
   const int m0 = blockIdx.y * RT, n0 = blockIdx.x * RT;
   int kbeg = 0, kend = MODE == R_FWD ? p.d : MODE == R_DX ? p.E : p.T;
   if (MODE == R_DW) {
-    kbeg = blockIdx.z * RCHUNK;
-    kend = min(p.T, kbeg + RCHUNK);
+    kbeg = blockIdx.z * p.chunk;
+    kend = min(p.T, kbeg + p.chunk);
   }
   rfloatx16 acc[2][2];
 #pragma unroll
@@ -186,6 +187,45 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
 
   // a lane owns output row lane%32 of each 32 x 32 block and, per 8-column group g, the 4
   // columns 8g + 4*(lane/32) ..
+  if (MODE == R_DX && (N & 7) == 0) {
+    // dX is read, added to and written back.  In the MFMA layout an access would touch 32 rows
+    // with 8 bytes each; every wavefront turns its 32 x 64 blocks around through the (now free)
+    // operand tiles instead, so that a lane handles 8 consecutive columns of a row (16 bytes of
+    // bf16) and an instruction covers 8 rows x 128 bytes.
+    constexpr int LDT = 68;   // fp32 row of 64 columns + pad
+    float* const stg = reinterpret_cast<float*>(wave < 2 ? As : Bs) + (wave & 1) * (32 * LDT);
+    uint16_t* const dXp = static_cast<uint16_t*>(p.dX);
+    const int r32 = lane & 31, hw = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(stg + r32 * LDT + 32 * j + 8 * g + 4 * hw) =
+              make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): the block is in LDS (wavefront-private area)
+      const int col = n0 + wn * 64 + (lane & 7) * 8;
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int rr = it * 8 + (lane >> 3);
+        const int row = m0 + wm * 64 + i * 32 + rr;
+        const float4 x0 = *reinterpret_cast<const float4*>(stg + rr * LDT + (lane & 7) * 8);
+        const float4 x1 = *reinterpret_cast<const float4*>(stg + rr * LDT + (lane & 7) * 8 + 4);
+        if (row < M && col < N) {
+          uint4* o = reinterpret_cast<uint4*>(dXp + (long long)row * N + col);
+          const uint4 old = *o;
+          *o = make_uint4(
+              pack_bf16x2(__uint_as_float(old.x << 16) + x0.x, __uint_as_float(old.x & 0xffff0000u) + x0.y),
+              pack_bf16x2(__uint_as_float(old.y << 16) + x0.z, __uint_as_float(old.y & 0xffff0000u) + x0.w),
+              pack_bf16x2(__uint_as_float(old.z << 16) + x1.x, __uint_as_float(old.z & 0xffff0000u) + x1.y),
+              pack_bf16x2(__uint_as_float(old.w << 16) + x1.z, __uint_as_float(old.w & 0xffff0000u) + x1.w));
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // the next block's writes must not pass these reads
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int row = m0 + wm * 64 + i * 32 + (lane & 31);
@@ -336,7 +376,13 @@ extern "C" int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* W
     RouterParams p = {};
     p.X = X; p.Wr = Wr; p.dl = dlogits; p.dX = dX; p.T = T; p.E = E; p.d = d;
     p.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + L.router_partial);
-    const int nchunk = cdiv(T, RCHUNK);
+    // chunks of 512 tokens, doubled while that leaves more than 1024 workgroups: fewer partial
+    // products to write and read back (a function of the configuration only: same bits every run)
+    const int tiles = cdiv(d, RT) * cdiv(E, RT);
+    int chunk = RCHUNK;
+    while ((long long)cdiv(T, chunk) * tiles > 1024 && chunk < 16384) chunk *= 2;
+    p.chunk = chunk;
+    const int nchunk = cdiv(T, chunk);
     if (T > 0) {
       SYMI_TIMED(K_ROUTER_DX, st, (router_gemm_kernel<R_DX><<<dim3(cdiv(d, RT), cdiv(T, RT)), 256, 0, st>>>(p)));
       SYMI_TIMED(K_ROUTER_DW, st, (router_gemm_kernel<R_DW><<<dim3(cdiv(d, RT), cdiv(E, RT), nchunk), 256, 0, st>>>(p)));
