@@ -114,10 +114,13 @@ def check_iteration(st: Hn.State, X, logits, dY, hp_kw=None, check_float=True):
     before = np.concatenate([W1s0.reshape(c.S_tot, -1), W2s0.reshape(c.S_tot, -1)], 1)
     sl = Hn.npf(slots)
     assert (sl[:, :lo] == before[:, :lo]).all() and (sl[:, lo + per:] == before[:, lo + per:]).all()
-    # and close to the oracle's slots (1 bf16 ulp where fp32 rounding straddles a tie)
+    # and close to the oracle's slots: the two master weights differ by at most the Adam
+    # tolerance (relative to max(|w|, rms), which matters for weights the step moves to ~0) and
+    # their bf16 roundings by one more ulp where that difference straddles a rounding boundary
     so = np.concatenate([W1s_o.reshape(c.S_tot, -1), W2s_o.reshape(c.S_tot, -1)], 1)
     if c.dtype == "bf16":
-        assert (np.abs(sl - so) <= 2.0 ** -7 * np.abs(so) + 1e-30).all()
+        rms = float(np.sqrt(np.mean(so[:, lo:lo + per] ** 2))) if per else 0.0
+        assert (np.abs(sl - so) <= 2.0 ** -7 * np.abs(so) + 2 * TOL["adam"] * rms + 1e-30).all()
     else:
         assert relerr_elem(sl, so) <= TOL["adam"]
 
