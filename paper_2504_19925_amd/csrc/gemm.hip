@@ -860,7 +860,7 @@ static void launch_gemm(const symi_cfg* cfg, const GemmParams& p, int n_cols, in
     dim3 grid(ntx, MODE <= BWD_DX ? max_mtiles + extra : cdiv(p.M, BM), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
     SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_bf16_kernel<MODE><<<grid, GT, 0, st>>>(p)));
     if (may_slice)   // the sliced round holds at most cus / 2 tiles
-      SYMI_TIMED(K_SLICE_SUM, st, (slice_sum_kernel<<<dim3(BM / 16, p.cus / 2), 256, 0, st>>>(p, ntx)));
+      SYMI_TIMED(K_SLICE_SUM, st, (slice_sum_kernel<<<dim3(BM / 16, std::max(1, p.cus / 2)), 256, 0, st>>>(p, ntx)));
   } else {
     const int bn = MODE == FWD1 ? FB / 2 : FB;
     dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 4 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
