@@ -69,7 +69,10 @@ typedef struct symi_adam {
 /* Host-only checks of a configuration (no GPU needed). */
 int symi_validate(const symi_cfg* cfg);
 /* Bytes of device workspace `ws` that symi_dispatch / symi_expert_fwd /
- * symi_expert_bwd / symi_router_bwd need for this configuration (0 if cfg is invalid). */
+ * symi_expert_bwd / symi_router_bwd need for this configuration (0 if cfg is invalid).
+ * The workspace is scratch: nothing in it has to survive from one call to the next, its
+ * contents need no initialisation, and two calls that may run at the same time (on different
+ * streams) must not share one. */
 size_t symi_workspace_bytes(const symi_cfg* cfg);
 const char* symi_last_error(void);
 
