@@ -5,13 +5,16 @@ A step is one pass of the whole hot path over one batch of synthetic input alrea
 resident in HBM: route -> dispatch -> expert forward -> combine -> combine backward ->
 expert backward -> dispatch backward -> route backward -> place (next placement) ->
 Adam on this GPU's 1/N shard + write into the next placement's replica slots.  The
-default workload is config c2 of the benchmark spec (bf16, E=64, top-2, d=1024, f=4096,
-T=8192, 96 slots, N=8, Zipf-1.2 popularity whose ranking is reshuffled every iteration);
-steps cycle through its 10 iterations.
+default workload is config c5 of the benchmark spec, the largest one (bf16, E=128, top-8,
+d=4096, f=2048, T=65536, 256 slots, N=32, near-uniform Zipf-0.5 popularity); --config
+picks another (c2 and c4 cycle through their 10 / 20 iterations).  All N optimizer
+partitions step during the warm-up, so that the timed steps start from the method's
+state; a timed step runs this GPU's partition only (the other N-1 live on other GPUs).
 
 Prints ONE JSON line: whole-job tokens/s, the roofline of the dominant kernel (from HIP
-events recorded around every launch inside the timed region) and the CPU oracle timed on
-a bounded sample of the same workload.
+events recorded around every launch of the timed steps run a second time), the step
+times and Adam rates of the other four configs (`other_configs`), and the CPU oracle
+timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -75,10 +78,10 @@ def survival(args):
     import torch
     import paper_2504_19925_amd as symi
     import workloads as wl
-    from tests import harness as Hn
+    import harness as Hn
 
     c = wl.get_config(args.config)
-    cfg = Hn.make_cfg(c)
+    cfg = Hn.make_ctx(c)
     dev = "cuda"
     i32 = dict(dtype=torch.int32, device=dev)
     ws = torch.empty(symi.symi_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
@@ -110,11 +113,11 @@ def extras(args):
     import torch
     import paper_2504_19925_amd as symi
     import workloads as wl
-    from tests import harness as Hn
+    import harness as Hn
 
     c = wl.get_config(args.config)
-    st = Hn.State(c)
-    s, cfg = st, st.cfg
+    st = Hn.State(c, flags=symi.CTX_TIMING | symi.CTX_NO_OVERLAP)
+    s, cfg = st, st.ctx
     X, logits, dY = Hn.draw_inputs(c, 0)
     st.place_current()
     st.forward(X, logits)
@@ -143,26 +146,22 @@ def extras(args):
         symi.symi_replica_allreduce(cfg, s.first_slot, 1.0, g1, g2)
 
     symi.symi_combine_bwd(cfg, dY, s.Yp, s.row_of_assign, s.gate, s.dYp, s.dgate)
-    symi.symi_set_overlap(False)
     out = {"workload": c.name, "unit": "us per call, all launches of a kernel id summed", "steps": args.steps}
     for fn in (router, fused, drawn):
         for _ in range(2):
             fn()
         Hn.sync()
-        symi.symi_timing_reset()
-        symi.symi_timing_enable(True)
+        symi.symi_timing_reset(cfg)
         for _ in range(args.steps):
             fn()
         Hn.sync()
-        symi.symi_timing_enable(False)
         got = {}
         for kid in range(symi.symi_kernel_count()):
-            ms, n = symi.symi_timing_read(kid)
+            ms, n = symi.symi_timing_read(cfg, kid)
             if n:
                 got[symi.symi_kernel_name(kid)] = round(ms / args.steps * 1e3, 1)
         got["total"] = round(sum(got.values()), 1)
         out[fn.__name__] = got
-    symi.symi_set_overlap(True)
     w = 2 if c.dtype == "bf16" else 4
     out["router_floor_us_at_8TBps"] = {"fwd": round(c.T * c.d * w / 8e6, 1),
                                        "dx": round((2 * c.T * c.d * w + 4 * c.T * c.E) / 8e6, 1),
@@ -182,49 +181,45 @@ def calibrate_copy():
     print(json.dumps({"copy_bytes_read": 2 * n, "copy_bytes_written": 2 * n, "copies": 8}))
 
 
-def run_gpu(args):
+def measure(c, args, steps, warmup):
+    """Times `steps` steps of workload c after `warmup` untimed ones; returns the figures of
+    the JSON line for that workload."""
     import torch
     import paper_2504_19925_amd as symi
-    import workloads as wl
-    from tests import harness as Hn
+    import harness as Hn
 
-    c = wl.get_config(args.config)
-    torch.cuda.set_device(0)
-    st = Hn.State(c, shard=0)
+    flags = symi.CTX_NO_OVERLAP if args.no_overlap else 0
+    # all N optimizer partitions are held and step during the warm-up (every slot is then
+    # whole, as after the N ranks of the method); partition 0 is this GPU's
+    st = Hn.State(c, shard=0, all_shards=True, flags=flags)
     st.active_grads = not args.dense_grads
+    # second context for the per-kernel table: HIP events around every launch, one stream
+    ctx_plain = st.ctx
+    ctx_timed = Hn.make_ctx(c, 0, 1, symi.CTX_TIMING | symi.CTX_NO_OVERLAP)
     iters = max(c.iters, 1)
     inputs = [Hn.draw_inputs(c, it) for it in range(iters)]
     adam, _ = Hn.make_adam()
     st.place_current()            # placement of iteration 0 (uniform) + slot weights
     Hn.sync()
 
-    def step(i):
+    def use(ctx):
+        st.ctx = ctx
+        st.opt[0] = (ctx,) + tuple(st.opt[0][1:])
+
+    def step(i, shards=(0,)):
         X, logits, dY = inputs[i % iters]
         st.forward(X, logits)
         st.backward(dY, logits)
-        st.optimizer(adam)
+        st.optimizer(adam, shards=shards)
         st.advance()   # the placement computed in this step is the one the next step dispatches with
 
-    def timed(n_steps, first, events):
-        """n_steps steps, optionally with a HIP event pair around every launch; returns ms per
-        step and {kernel: (average ms per launch, launches)}."""
-        Hn.sync()
-        symi.symi_timing_reset()
-        symi.symi_timing_enable(events)
+    def timed(n_steps, first):
         Hn.sync()
         t0 = time.perf_counter()
         for i in range(n_steps):
             step(first + i)
         Hn.sync()
-        t1 = time.perf_counter()
-        symi.symi_timing_enable(False)
-        got = {}
-        for kid in range(symi.symi_kernel_count()):
-            ms, n = symi.symi_timing_read(kid)
-            if n:
-                got[symi.symi_kernel_name(kid)] = (ms / n, n)
-        symi.symi_timing_reset()
-        return (t1 - t0) * 1e3 / n_steps, got
+        return (time.perf_counter() - t0) * 1e3 / n_steps
 
     def timed_graphs(n_steps, first):
         """The same n_steps steps replayed from HIP graphs: one graph per distinct step (the
@@ -255,28 +250,37 @@ def run_gpu(args):
         del graphs
         return (t1 - t0) * 1e3 / n_steps
 
-    symi.symi_set_overlap(not args.no_overlap)
-    for i in range(args.warmup):
-        step(i)
+    for i in range(warmup):
+        step(i, shards=None)
     # the timed region: the library as it ships, nothing but the K steps between two
     # synchronisations (no events: a pair around each of the ~20 launches of a step costs 6 % on
     # c2; the backward's two chains of products may share the chip on two streams)
     if args.graph:
-        ms_per_step = timed_graphs(args.steps, args.warmup)
+        ms_per_step = timed_graphs(steps, warmup)
     else:
-        ms_per_step, _ = timed(args.steps, args.warmup, False)
-    # per-kernel durations and the roofline come from the same steps run again with HIP events
-    # around every launch and one kernel at a time on the stream, which is also what the
-    # committed rocprofv3 summary shows
-    symi.symi_set_overlap(False)
-    ms_serial, times = timed(args.steps, args.warmup, True)
-    symi.symi_set_overlap(not args.no_overlap)
+        ms_per_step = timed(steps, warmup)
+    # per-kernel durations and the roofline come from the same steps run again through a context
+    # that records HIP events around every launch and keeps one kernel at a time on the stream,
+    # which is also what the committed rocprofv3 summary shows
+    use(ctx_timed)
+    step(warmup + steps)
+    step(warmup + steps + 1)
+    Hn.sync()
+    symi.symi_timing_reset(ctx_timed)
+    ms_serial = timed(steps, warmup)
+    times = {}
+    for kid in range(symi.symi_kernel_count()):
+        ms, n = symi.symi_timing_read(ctx_timed, kid)
+        if n:
+            times[symi.symi_kernel_name(kid)] = (ms / n, n)
+    symi.symi_timing_reset(ctx_timed)
+    use(ctx_plain)
     w = 2 if c.dtype == "bf16" else 4
 
     # slots that actually hold rows (their weights are the ones a step must read)
     nonempty, active = [], []
     for i in range(iters):
-        step(args.warmup + args.steps + i)
+        step(warmup + i)
         Hn.sync()
         so = st.slot_offsets.cpu()
         nonempty.append(int((so[1:] > so[:-1]).sum()))
@@ -288,16 +292,16 @@ def run_gpu(args):
     peak_tf = MFMA_BF16_PEAK_TF if c.dtype == "bf16" else FP32_VEC_PEAK_TF
     kernels = {}
     for name, (avg_ms, n) in times.items():
-        entry = {"avg_us": round(avg_ms * 1e3, 2), "launches_per_step": round(n / args.steps, 2)}
+        entry = {"avg_us": round(avg_ms * 1e3, 2), "launches_per_step": round(n / steps, 2)}
         if name in work:
             fl, by = work[name]
             entry["GB/s"] = round(by / (avg_ms * 1e-3) / 1e9, 1)
             if fl:
                 entry["TFLOP/s"] = round(fl / (avg_ms * 1e-3) / 1e12, 1)
         kernels[name] = entry
-    gpu_ms = sum(avg * n for avg, n in times.values()) / args.steps
+    gpu_ms = sum(avg * n for avg, n in times.values()) / steps
     fb = [k_ for k_ in times if k_ not in ("place", "adam_to_replicas")]
-    fwd_bwd_ms = sum(times[k_][0] * times[k_][1] for k_ in fb) / args.steps
+    fwd_bwd_ms = sum(times[k_][0] * times[k_][1] for k_ in fb) / steps
 
     dom = max((k_ for k_ in times if k_ in work), key=lambda k_: times[k_][0] * times[k_][1])
     fl, by = work[dom]
@@ -319,7 +323,7 @@ def run_gpu(args):
         "metric": "MoE layer fwd+bwd tokens/s; grouped-GEMM MFMA %; Adam+scatter HBM GB/s",
         "value": round(c.T / (ms_per_step * 1e-3), 1),
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": c.dtype, "data": "synthetic",
@@ -334,18 +338,42 @@ def run_gpu(args):
         "fwd_bwd_tokens_per_s": round(c.T / (fwd_bwd_ms * 1e-3), 1),
         "gpu_kernel_ms_per_step": round(gpu_ms, 4),
         "ms_per_step_second_pass": round(ms_serial, 4),
-        "kernel_table": "second pass of the same steps: HIP events around every launch, symi_set_overlap(0)",
+        "kernel_table": "second pass of the same steps: a context with SYMI_CTX_TIMING | SYMI_CTX_NO_OVERLAP",
         "launch": "HIP graph replay" if args.graph else "host launches",
         "nonempty_slots_mean": round(mean_nonempty, 2),
         "classes_with_tokens_mean": round(mean_active, 2),
         "kernels": kernels,
     }
-    return out, c
+    del st, inputs
+    torch.cuda.empty_cache()
+    return out
 
 
-def cpu_baseline(c, seconds_hint=20.0):
-    """The oracle as it stands, timed on a bounded sample of the same workload."""
+def summary(out):
+    """The few figures of another workload that ride along on the main line."""
+    ks = out["kernels"]
+    gemm = {n: e["TFLOP/s"] for n, e in ks.items() if n.startswith("gemm_") and "TFLOP/s" in e}
+    peak = MFMA_BF16_PEAK_TF if out["dtype"] == "bf16" else FP32_VEC_PEAK_TF
+    s = {"ms_per_step": out["ms_per_step"], "tokens_per_s": out["value"], "steps": out["steps"],
+         "fwd_bwd_tokens_per_s": out["fwd_bwd_tokens_per_s"]}
+    if "adam_to_replicas" in ks:
+        s["adam_GB/s"] = ks["adam_to_replicas"]["GB/s"]
+        s["adam_frac_of_hbm"] = round(ks["adam_to_replicas"]["GB/s"] / HBM_PEAK_GBS, 4)
+    if gemm:
+        s["gemm_TFLOP/s"] = gemm
+        s["gemm_frac_of_peak_min_max"] = [round(min(gemm.values()) / peak, 4), round(max(gemm.values()) / peak, 4)]
+    for n in ("gather_rows", "combine", "dispatch_bwd", "route"):
+        if n in ks and "GB/s" in ks[n]:
+            s[n + "_GB/s"] = ks[n]["GB/s"]
+    return s
+
+
+def cpu_baseline(c):
+    """The oracle as it stands, timed on a bounded sample of the same workload: whole
+    iterations on the first Ts tokens (all classes, full widths), Ts chosen so that one
+    sampled iteration is about 1.5 TFLOP of fp64 work."""
     import numpy as np
+    import torch
     import workloads as wl
     from oracle import symi_oracle as O
     try:
@@ -354,22 +382,34 @@ def cpu_baseline(c, seconds_hint=20.0):
     except Exception:
         cores = os.cpu_count() or 1
 
-    Ts = min(c.T, 8192)                      # tokens of the sample (all E classes, full d, f)
+    per_token = 18.0 * c.k * c.d * c.f
+    Ts = c.T
+    while Ts > 256 and Ts * per_token > 1.5e12:
+        Ts //= 2
     Es = min(c.E, 64)                        # classes whose shard the sampled Adam step covers
-    W1, W2 = wl.make_class_weights(c, "cpu")
-    W1, W2 = W1.float().numpy(), W2.float().numpy()
+    dev = "cuda" if torch.cuda.is_available() else "cpu"     # where the inputs are drawn, nothing else
+    W1g, W2g = wl.make_class_weights(c, dev)
+    W1 = np.empty(tuple(W1g.shape), np.float32)
+    W2 = np.empty(tuple(W2g.shape), np.float32)
+    for e in range(c.E):
+        W1[e] = W1g[e].float().cpu().numpy()
+        W2[e] = W2g[e].float().cpu().numpy()
+    del W1g, W2g
     per = c.P_e // c.N
     hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, grad_scale=1.0, step=1)
-    flat = np.concatenate([W1[:Es].reshape(Es, -1), W2[:Es].reshape(Es, -1)], 1)[:, :per]
+    n1 = 2 * c.f * c.d                        # partition 0 owns [0, per) of the flat vector [W1 | W2]
+    flat = np.concatenate([W1[:Es].reshape(Es, -1)[:, :min(per, n1)],
+                           W2[:Es].reshape(Es, -1)[:, :max(per - n1, 0)]], 1).copy()
     hist_prev = np.zeros(c.E, dtype=np.int64)
     t_layer = t_adam = 0.0
     n_it = 0
     # whole iterations of the workload until about 10 s of oracle time are spent (at most 3)
     for it in range(min(max(c.iters, 1), 3)):
-        X = wl.make_tokens(c, it, "cpu")[:Ts].float().numpy()
-        z = wl.make_logits(c, it, "cpu")[:Ts].numpy() if not c.router_matmul else \
-            wl.make_logits(c, it, "cpu", tokens=wl.make_tokens(c, it, "cpu"))[:Ts].numpy()
-        dY = wl.make_upstream_grad(c, it, "cpu")[:Ts].float().numpy()
+        Xt = wl.make_tokens(c, it, dev)
+        X = Xt[:Ts].float().cpu().numpy()
+        z = wl.make_logits(c, it, dev, tokens=Xt)[:Ts].cpu().numpy()
+        dY = wl.make_upstream_grad(c, it, dev)[:Ts].float().cpu().numpy()
+        del Xt
         t0 = time.perf_counter()
         idx, gate, hist = O.route(z, c.k, True)
         counts, placement, first = O.place(hist_prev, c.S_tot)
@@ -386,6 +426,7 @@ def cpu_baseline(c, seconds_hint=20.0):
         O.adam_to_replicas(dW1[:Es], dW2[:Es], flat, np.zeros_like(flat), np.zeros_like(flat), sub_place,
                            c.N, 0, hp, c.dtype == "bf16", W1s, W2s)
         t_adam += time.perf_counter() - t0
+        del dX, dW1, dW2, W1s, W2s
         hist_prev = hist
         n_it += 1
         if t_layer + t_adam >= 10.0:
@@ -403,10 +444,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c2")
+    ap.add_argument("--config", default="c5")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of the other four workloads that ride along on the line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true",
-                    help="keep every kernel on one stream also in the timed region (symi_set_overlap(0))")
+                    help="keep every kernel on one stream also in the timed region (SYMI_CTX_NO_OVERLAP)")
     ap.add_argument("--graph", action="store_true",
                     help="timed region replays the steps from captured HIP graphs instead of launching "
                          "every kernel from the host")
@@ -435,7 +478,19 @@ def main():
         print("bench.py: this build measures one GPU's share of the path; --gpus must be 1 "
               "(no collectives are part of it)", file=sys.stderr)
         sys.exit(2)
-    out, c = run_gpu(args)
+    import torch
+    import workloads as wl
+    torch.cuda.set_device(0)
+    c = wl.get_config(args.config)
+    out = measure(c, args, args.steps, args.warmup)
+    if not args.no_other_configs:
+        # the other workloads, briefly (each one whole cycle of its iterations at least)
+        out["other_configs"] = {}
+        for name in sorted(wl.CONFIGS):
+            if name == c.name:
+                continue
+            o = wl.get_config(name)
+            out["other_configs"][name] = summary(measure(o, args, max(20, o.iters), 5))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(c)
     print(json.dumps(out))

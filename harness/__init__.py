@@ -19,6 +19,11 @@ def make_cfg(c: wl.Config, shard=0, renorm=1):
     return symi.SymiCfg.make(c.T, c.E, c.k, c.d, c.f, c.S_tot, c.N, shard, c.dtype, renorm)
 
 
+def make_ctx(c: wl.Config, shard=0, renorm=1, flags=0):
+    """A library context (symi_create) for workload c on the current device."""
+    return symi.symi_create(make_cfg(c, shard, renorm), flags)
+
+
 def make_adam(**kw):
     hp = dict(HP)
     hp.update(kw)
@@ -31,10 +36,15 @@ def make_adam(**kw):
 class State:
     """Buffers that persist across iterations of one config (all on the GPU)."""
 
-    def __init__(self, c: wl.Config, dev="cuda", shard=0, renorm=1, weights=None):
+    def __init__(self, c: wl.Config, dev="cuda", shard=0, renorm=1, weights=None, flags=0,
+                 all_shards=False):
+        """shard: the optimizer partition this state's context (and .master/.m/.v) belongs to.
+        all_shards: also hold the other N-1 partitions (contexts and Adam state), so that
+        optimizer() rewrites the whole of every slot, as the N ranks of the method do."""
         self.c, self.dev = c, dev
         self.active_grads = False   # True: the *_active pair (classes without rows are skipped)
-        self.cfg = make_cfg(c, shard, renorm)
+        self.ctx = make_ctx(c, shard, renorm, flags)
+        self.cfg = self.ctx.cfg
         dt = self.cfg.torch_dtype
         i32 = dict(dtype=torch.int32, device=dev)
         E, S, A, T, d, f = c.E, c.S_tot, c.A, c.T, c.d, c.f
@@ -65,54 +75,64 @@ class State:
         self.W2s = torch.empty(S, d, f, dtype=dt, device=dev)
         # this partition's optimizer state: master weights start as the class weights
         per = c.P_e // c.N
-        lo = shard * per
-        flat = torch.cat([self.W1c.reshape(E, -1), self.W2c.reshape(E, -1)], dim=1)
-        self.master = flat[:, lo:lo + per].to(torch.float32).contiguous()
-        del flat
-        self.m = torch.zeros_like(self.master)
-        self.v = torch.zeros_like(self.master)
+        self.opt = {}     # shard -> (context, master, m, v)
+        for n in (range(c.N) if all_shards else [shard]):
+            lo = n * per
+            n1 = 2 * f * d
+            parts = []
+            if lo < n1:
+                parts.append(self.W1c.reshape(E, -1)[:, lo:min(lo + per, n1)])
+            if lo + per > n1:
+                parts.append(self.W2c.reshape(E, -1)[:, max(lo - n1, 0):lo + per - n1])
+            master = torch.cat(parts, dim=1).to(torch.float32).contiguous()
+            ctx_n = self.ctx if n == shard else make_ctx(c, n, renorm, symi.CTX_NO_OVERLAP)
+            self.opt[n] = (ctx_n, master, torch.zeros_like(master), torch.zeros_like(master))
+        _, self.master, self.m, self.v = self.opt[shard]
 
     def place_current(self):
         """Placement of the coming iteration from the previous iteration's popularity,
         and slot weights materialised from the class weights (every replica of a class
         holds the same weights)."""
-        symi.symi_place(self.cfg, self.hist_prev, self.counts, self.placement, self.first_slot)
+        symi.symi_place(self.ctx, self.hist_prev, self.counts, self.placement, self.first_slot)
         pl = self.placement.long()
         torch.index_select(self.W1c, 0, pl, out=self.W1s)
         torch.index_select(self.W2c, 0, pl, out=self.W2s)
 
     def forward(self, X, logits, slot_cap=None):
         """slot_cap: rows a slot may take (capacity-limited dispatch); None = dropless."""
-        s, cfg = self, self.cfg
-        symi.symi_route(cfg, logits, s.idx, s.gate, s.hist)
+        s, ctx = self, self.ctx
+        symi.symi_route(ctx, logits, s.idx, s.gate, s.hist)
         if slot_cap is None:
-            symi.symi_dispatch(cfg, X, s.idx, s.hist, s.counts, s.first_slot, s.row_of_assign,
+            symi.symi_dispatch(ctx, X, s.idx, s.hist, s.counts, s.first_slot, s.row_of_assign,
                                s.assign_of_row, s.slot_offsets, s.Xp, s.ws)
         else:
-            symi.symi_dispatch_capacity(cfg, slot_cap, X, s.idx, s.hist, s.counts, s.first_slot,
+            symi.symi_dispatch_capacity(ctx, slot_cap, X, s.idx, s.hist, s.counts, s.first_slot,
                                         s.row_of_assign, s.assign_of_row, s.slot_offsets, s.Xp, s.ws)
-        symi.symi_expert_fwd(cfg, s.Xp, s.slot_offsets, s.W1s, s.W2s, s.UV, s.H, s.Yp, s.ws)
-        symi.symi_combine(cfg, s.Yp, s.row_of_assign, s.gate, s.Y)
+        symi.symi_expert_fwd(ctx, s.Xp, s.slot_offsets, s.W1s, s.W2s, s.UV, s.H, s.Yp, s.ws)
+        symi.symi_combine(ctx, s.Yp, s.row_of_assign, s.gate, s.Y)
 
     def backward(self, dY, logits):
-        s, cfg = self, self.cfg
-        symi.symi_combine_bwd(cfg, dY, s.Yp, s.row_of_assign, s.gate, s.dYp, s.dgate)
+        s, ctx = self, self.ctx
+        symi.symi_combine_bwd(ctx, dY, s.Yp, s.row_of_assign, s.gate, s.dYp, s.dgate)
         bwd = symi.symi_expert_bwd_active if s.active_grads else symi.symi_expert_bwd
-        bwd(cfg, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
+        bwd(ctx, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
             s.dXp, s.dW1, s.dW2, s.ws)
-        symi.symi_dispatch_bwd(cfg, s.dXp, s.row_of_assign, s.dX)
-        symi.symi_route_bwd(cfg, logits, s.idx, s.gate, s.dgate, s.dlogits)
+        symi.symi_dispatch_bwd(ctx, s.dXp, s.row_of_assign, s.dX)
+        symi.symi_route_bwd(ctx, logits, s.idx, s.gate, s.dgate, s.dlogits)
 
-    def optimizer(self, adam):
-        s, cfg = self, self.cfg
-        symi.symi_place(cfg, s.hist, s.counts_next, s.placement_next, s.first_slot_next)
-        if s.active_grads:   # gradients of classes without rows were not written: do not read them
-            symi.symi_adam_to_replicas_active(cfg, adam, s.dW1, s.dW2, s.master, s.m, s.v,
-                                              s.slot_offsets, s.first_slot, s.first_slot_next,
-                                              s.W1s, s.W2s)
-        else:
-            symi.symi_adam_to_replicas(cfg, adam, s.dW1, s.dW2, s.master, s.m, s.v, s.first_slot_next,
-                                       s.W1s, s.W2s)
+    def optimizer(self, adam, shards=None):
+        """Next placement, then Adam + replica write for the held partitions (or `shards`)."""
+        s = self
+        symi.symi_place(s.ctx, s.hist, s.counts_next, s.placement_next, s.first_slot_next)
+        for n in (s.opt if shards is None else shards):
+            ctx, master, m, v = s.opt[n]
+            if s.active_grads:   # gradients of classes without rows were not written: do not read them
+                symi.symi_adam_to_replicas_active(ctx, adam, s.dW1, s.dW2, master, m, v,
+                                                  s.slot_offsets, s.first_slot, s.first_slot_next,
+                                                  s.W1s, s.W2s)
+            else:
+                symi.symi_adam_to_replicas(ctx, adam, s.dW1, s.dW2, master, m, v, s.first_slot_next,
+                                           s.W1s, s.W2s)
 
     def advance(self):
         """The placement computed by optimizer() becomes the one the next iteration dispatches

@@ -7,6 +7,7 @@
  *   forward    symi_route -> symi_dispatch (or symi_dispatch_capacity) -> symi_expert_fwd -> symi_combine
  *   backward   symi_combine_bwd -> symi_expert_bwd -> symi_dispatch_bwd -> symi_route_bwd
  *   optimizer  symi_place (next placement, Algorithm 1) -> symi_adam_to_replicas
+ *   set-up     symi_create (one context per MoE layer and optimizer partition) ... symi_destroy
  *   optional   symi_router_fwd before symi_route, symi_router_bwd after symi_route_bwd;
  *              symi_expert_bwd_slots + symi_replica_allreduce instead of symi_expert_bwd;
  *              symi_expert_bwd_active + symi_adam_to_replicas_active instead of the plain
@@ -17,12 +18,15 @@
  *   - Every function returns 0 (SYMI_OK) or a negative error code; symi_last_error()
  *     returns a description of the most recent failure on the calling thread.
  *   - Unless a parameter says "host", every pointer is a DEVICE pointer owned by the
- *     caller, valid until the work enqueued on `stream` has finished.  The library
- *     allocates no memory and never synchronises with the host inside these calls (the
- *     only objects it creates are one helper stream and three events per device, at the
- *     first symi_expert_bwd call; see symi_set_overlap).  Calls are not thread-safe.
- *     The device calls can be captured into a HIP graph (no memsets, no host synchronisation);
- *     call symi_expert_bwd once eagerly first, so that its helper stream exists.
+ *     caller, valid until the work enqueued on `stream` has finished.  The device calls
+ *     allocate nothing, create nothing and never synchronise with the host: everything the
+ *     library owns (the validated configuration, a helper stream and three events for the
+ *     backward where the shape calls for them) is made by symi_create and lives in the opaque
+ *     symi_ctx until symi_destroy.  There is no process-wide state: calls on different
+ *     contexts may run on different threads; calls on one context must not overlap.
+ *     The device calls can be captured into a HIP graph (no memsets, no host synchronisation).
+ *   - `ctx` is a HOST pointer from symi_create; every device call checks that the device it
+ *     was created on is the current one (SYMI_EINVAL otherwise).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - `cfg` and `hp` are HOST pointers, read during the call only.
  *   - Activations and slot weights are fp32 or bf16 according to cfg->dtype; routing
@@ -33,7 +37,9 @@
  *     d model width, f FFN width, P_e = 3*d*f parameters per expert.
  *   - Shape limits checked by symi_validate: 1 <= k <= min(E, 16), E <= 1024,
  *     E <= S_tot <= 4096, P_e divisible by N, 0 <= shard < N; d, f and P_e/N
- *     multiples of 8.
+ *     multiples of 8.  Beyond the launch limits of the kernels (SYMI_EUNSUPPORTED):
+ *     T*k/256 + S_tot + 256 <= 65535 m-tiles (fp32: 4*(T*k/256 + S_tot) <= 65535),
+ *     T/128 <= 65535, 2*f*d < 2^31.
  */
 #ifndef SYMI_H
 #define SYMI_H
@@ -68,6 +74,32 @@ typedef struct symi_adam {
 
 /* Host-only checks of a configuration (no GPU needed). */
 int symi_validate(const symi_cfg* cfg);
+
+/* The per-layer state of Fig. 5 that is not a tensor: an opaque, immutable context holding the
+ * validated configuration of one MoE layer and optimizer partition (cfg->shard) together with
+ * what the library needs to run it on the CURRENT device (queried once: compute units; created
+ * once: the helper stream and events of the expert backward, only when the shape makes the two
+ * gradient chains worth two streams).  Host function; the only one that creates anything.
+ *   flags: 0 or an OR of
+ *     SYMI_CTX_NO_OVERLAP  every kernel of symi_expert_bwd* stays on the caller's stream
+ *                          (default: the weight-gradient chain runs on the helper stream,
+ *                          forked from and joined back into `stream` with events, when the
+ *                          products are only a few rounds of workgroups: for the caller
+ *                          everything is still ordered on `stream`);
+ *     SYMI_CTX_NO_SLICING  the two narrow products (Yp = H W2^T, dXp = dUV W1) never cut the
+ *                          reduction of their last round's tiles into slices (default: they
+ *                          do when that round would leave at least half the compute units
+ *                          idle, and add the slices up in a fixed order: same bits on every
+ *                          run, not the bits of the uncut reduction);
+ *     SYMI_CTX_TIMING      measurement aid, see symi_timing_read.
+ *   Neither of the first two changes what is computed beyond rounding order.
+ * Errors: SYMI_EINVAL / SYMI_EUNSUPPORTED as symi_validate, SYMI_EHIP without a usable device.
+ * symi_destroy(NULL) is a no-op; destroying a context does not wait for work in flight: the
+ * caller synchronises first. */
+typedef struct symi_ctx symi_ctx;
+enum { SYMI_CTX_NO_OVERLAP = 1, SYMI_CTX_NO_SLICING = 2, SYMI_CTX_TIMING = 4 };
+int symi_create(const symi_cfg* cfg, unsigned flags, symi_ctx** out);
+int symi_destroy(symi_ctx* ctx);
 /* Bytes of device workspace `ws` that symi_dispatch / symi_expert_fwd /
  * symi_expert_bwd / symi_router_bwd need for this configuration (0 if cfg is invalid).
  * The workspace is scratch: nothing in it has to survive from one call to the next, its
@@ -82,11 +114,13 @@ const char* symi_last_error(void);
  *   first, equal scores resolved towards the lower class index.  gate [T,k] f32 out:
  *   softmax over all E classes evaluated at idx, divided by their sum if cfg->renorm.
  *   hist [E] i32 out: number of (token, choice) pairs per class; sums to T*k.       */
-int symi_route(const symi_cfg* cfg, const float* logits, int32_t* idx, float* gate,
+int symi_route(const symi_ctx* ctx, const float* logits, int32_t* idx, float* gate,
                int32_t* hist, void* stream);
 
-/* Backward of symi_route's gate: dlogits [T,E] f32 out from dgate [T,k] f32. */
-int symi_route_bwd(const symi_cfg* cfg, const float* logits, const int32_t* idx,
+/* Backward of the gating of Sec. 2.1 (softmax over all classes, top-k, optional
+ * renormalisation) as symi_route evaluates it: dlogits [T,E] f32 out from dgate [T,k] f32
+ * (the router is learned, Sec. 2.1, so its logits need a gradient). */
+int symi_route_bwd(const symi_ctx* ctx, const float* logits, const int32_t* idx,
                    const float* gate, const float* dgate, float* dlogits, void* stream);
 
 /* Expert Placement Scheduler, Algorithm 1 (App. A.3; Sec. 3.4), in exact integer
@@ -96,7 +130,7 @@ int symi_route_bwd(const symi_cfg* cfg, const float* logits, const int32_t* idx,
  *   popularity [E] i32 in (normally the previous iteration's hist).
  *   counts [E] i32 out (r_i), placement [S_tot] i32 out (slot -> class),
  *   first_slot [E+1] i32 out (prefix sums of counts).                               */
-int symi_place(const symi_cfg* cfg, const int32_t* popularity, int32_t* counts,
+int symi_place(const symi_ctx* ctx, const int32_t* popularity, int32_t* counts,
                int32_t* placement, int32_t* first_slot, void* stream);
 /* Same computation on HOST pointers (the paper runs the scheduler on every rank's CPU). */
 int symi_place_host(const symi_cfg* cfg, const int32_t* popularity, int32_t* counts,
@@ -109,7 +143,7 @@ int symi_place_host(const symi_cfg* cfg, const int32_t* popularity, int32_t* cou
  *   X [T,d] in; idx [T,k], hist [E] (this iteration's), counts [E], first_slot [E+1] in.
  *   row_of_assign [A], assign_of_row [A], slot_offsets [S_tot+1] i32 out;
  *   Xp [A,d] out: Xp[row] = X[assign_of_row[row] / k].                              */
-int symi_dispatch(const symi_cfg* cfg, const void* X, const int32_t* idx, const int32_t* hist,
+int symi_dispatch(const symi_ctx* ctx, const void* X, const int32_t* idx, const int32_t* hist,
                   const int32_t* counts, const int32_t* first_slot, int32_t* row_of_assign,
                   int32_t* assign_of_row, int32_t* slot_offsets, void* Xp, void* ws,
                   void* stream);
@@ -131,13 +165,14 @@ int symi_slot_capacity(const symi_cfg* cfg, double capacity_factor);
  * symi_expert_fwd/bwd work on slot_offsets and so on the kept rows only; symi_combine,
  * symi_combine_bwd and symi_dispatch_bwd skip dropped assignments (they contribute
  * nothing to Y, dX, and get dgate = 0); gates are not renormalised after a drop.        */
-int symi_dispatch_capacity(const symi_cfg* cfg, int slot_capacity, const void* X, const int32_t* idx,
+int symi_dispatch_capacity(const symi_ctx* ctx, int slot_capacity, const void* X, const int32_t* idx,
                            const int32_t* hist, const int32_t* counts, const int32_t* first_slot,
                            int32_t* row_of_assign, int32_t* assign_of_row, int32_t* slot_offsets,
                            void* Xp, void* ws, void* stream);
 
-/* Backward of the gather: dX[t] = sum_j dXp[row_of_assign[t*k+j]] (j ascending). */
-int symi_dispatch_bwd(const symi_cfg* cfg, const void* dXp, const int32_t* row_of_assign,
+/* Backward of Sec. 3.2 step 2 (the scatter of tokens to their replicas; the all-to-all of
+ * Sec. 2.1 run in reverse): dX[t] = sum_j dXp[row_of_assign[t*k+j]] (j ascending, fp32 sum). */
+int symi_dispatch_bwd(const symi_ctx* ctx, const void* dXp, const int32_t* row_of_assign,
                       void* dX, void* stream);
 
 /* Expert SwiGLU FFN over replica slots (Sec. 2.1; the expert compute of Fig. 5).
@@ -145,7 +180,7 @@ int symi_dispatch_bwd(const symi_cfg* cfg, const void* dXp, const int32_t* row_o
  *   u = x Wg^T, v = x Wu^T, h = silu(u)*v, y = h Wd^T
  *   W1_slots [S_tot,2f,d]: rows 0..f-1 = Wg, rows f..2f-1 = Wu; W2_slots [S_tot,d,f] = Wd.
  *   UV [A,2f] (u | v), H [A,f] and Yp [A,d] out (UV and H are kept for the backward). */
-int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_t* slot_offsets,
+int symi_expert_fwd(const symi_ctx* ctx, const void* Xp, const int32_t* slot_offsets,
                     const void* W1_slots, const void* W2_slots, void* UV, void* H, void* Yp,
                     void* ws, void* stream);
 
@@ -153,18 +188,20 @@ int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_t* slot_off
  * f32 out: the gradient of each class summed over ALL its rows, i.e. over all its
  * replica slots (the intra-rank part of the gradient all-reduce of Sec. 4.1); a class
  * without rows gets zeros.  first_slot [E+1] is the placement used by symi_dispatch. */
-int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
+int symi_expert_bwd(const symi_ctx* ctx, const void* dYp, const void* Xp, const void* UV,
                     const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
                     const void* W1_slots, const void* W2_slots, void* dXp, float* dW1_class,
                     float* dW2_class, void* ws, void* stream);
 
-/* Gate-weighted combine: Y[t] = sum_j gate[t,j] * Yp[row_of_assign[t*k+j]], j ascending,
+/* Sec. 2.1: the expert outputs return to their tokens (the gather all-to-all) and are mixed
+ * with the gate weights: Y[t] = sum_j gate[t,j] * Yp[row_of_assign[t*k+j]], j ascending,
  * accumulated in fp32.  Y [T,d] out. */
-int symi_combine(const symi_cfg* cfg, const void* Yp, const int32_t* row_of_assign,
+int symi_combine(const symi_ctx* ctx, const void* Yp, const int32_t* row_of_assign,
                  const float* gate, void* Y, void* stream);
 
-/* Backward of symi_combine: dYp[row] = gate[t,j]*dY[t]; dgate[t,j] = <dY[t], Yp[row]>. */
-int symi_combine_bwd(const symi_cfg* cfg, const void* dY, const void* Yp,
+/* Backward of that gather and mix (Sec. 2.1; the all-to-all scatter of the backward pass):
+ * dYp[row] = gate[t,j]*dY[t]; dgate[t,j] = <dY[t], Yp[row]>. */
+int symi_combine_bwd(const symi_ctx* ctx, const void* dY, const void* Yp,
                      const int32_t* row_of_assign, const float* gate, void* dYp, float* dgate,
                      void* stream);
 
@@ -178,7 +215,7 @@ int symi_combine_bwd(const symi_cfg* cfg, const void* dY, const void* Yp,
  * first_slot_next[e] .. first_slot_next[e+1]-1 of W1_slots / W2_slots: the placement of
  * the NEXT iteration.  Bytes written to slots are S_tot*P_e/N*sizeof(weight), whatever
  * the placement.  hp is a HOST pointer. */
-int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp, const float* dW1_class,
+int symi_adam_to_replicas(const symi_ctx* ctx, const symi_adam* hp, const float* dW1_class,
                           const float* dW2_class, float* master_w, float* m, float* v,
                           const int32_t* first_slot_next, void* W1_slots, void* W2_slots,
                           void* stream);
@@ -187,29 +224,15 @@ int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp, const float*
  * against every expert class), so that the layer is closed from X to dX:
  *   logits [T,E] f32 out = X Wr^T + b.   X [T,d], Wr [E,d] in the activation dtype (row e of
  *   Wr is class e's scoring vector), b [E] f32 or NULL.                                   */
-int symi_router_fwd(const symi_cfg* cfg, const void* X, const void* Wr, const float* b,
+int symi_router_fwd(const symi_ctx* ctx, const void* X, const void* Wr, const float* b,
                     float* logits, void* stream);
 
 /* Backward of symi_router_fwd from dlogits [T,E] f32 (symi_route_bwd's output):
  *   dWr [E,d] f32 out = dlogits^T X;  db [E] f32 out = column sums of dlogits (NULL: skipped);
  *   dX [T,d] IN/OUT: dlogits Wr is ADDED to it (call after symi_dispatch_bwd).
  * Deterministic: the reduction over tokens is cut into fixed chunks summed in order.      */
-int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* Wr, const float* dlogits,
+int symi_router_bwd(const symi_ctx* ctx, const void* X, const void* Wr, const float* dlogits,
                     float* dWr, float* db, void* dX, void* ws, void* stream);
-
-/* symi_expert_bwd / symi_expert_bwd_slots enqueue the weight-gradient products on a helper
- * stream of the library (one per device, created at the first call) that is forked from and
- * joined back into `stream` with events: for the caller everything is still ordered on
- * `stream`.  It does so when the products are only a few rounds of workgroups (small
- * batches); symi_set_overlap(0) keeps every kernel on `stream` itself, (1) is the default. */
-int symi_set_overlap(int on);
-
-/* symi_expert_fwd / symi_expert_bwd cut the reduction of the last round's tiles of the two
- * narrow products (Yp = H W2^T, dXp = dUV W1) into slices when that round would leave at
- * least half the compute units idle, and add the slices up in a fixed order (same bits on
- * every run; not the bits of the uncut reduction).  symi_set_slicing(0) turns that off,
- * (1) is the default. */
-int symi_set_slicing(int on);
 
 /* The same two calls for a batch that leaves many classes without tokens.  A rank of the
  * paper only ever forms gradients for the classes it hosts (Sec. 4.1; Algorithm 2 collects a
@@ -223,11 +246,11 @@ int symi_set_slicing(int on);
  *     class is taken as zero and its memory is not read.  slot_offsets [S_tot+1] and
  *     first_slot [E+1] are those of the iteration the gradients come from (device pointers).
  * Together they give bit for bit the master_w, m, v and slots of the plain pair.          */
-int symi_expert_bwd_active(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
+int symi_expert_bwd_active(const symi_ctx* ctx, const void* dYp, const void* Xp, const void* UV,
                            const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
                            const void* W1_slots, const void* W2_slots, void* dXp,
                            float* dW1_class, float* dW2_class, void* ws, void* stream);
-int symi_adam_to_replicas_active(const symi_cfg* cfg, const symi_adam* hp, const float* dW1_class,
+int symi_adam_to_replicas_active(const symi_ctx* ctx, const symi_adam* hp, const float* dW1_class,
                                  const float* dW2_class, float* master_w, float* m, float* v,
                                  const int32_t* slot_offsets, const int32_t* first_slot,
                                  const int32_t* first_slot_next, void* W1_slots, void* W2_slots,
@@ -237,7 +260,7 @@ int symi_adam_to_replicas_active(const symi_cfg* cfg, const symi_adam* hp, const
  * symi_expert_bwd's fused per-class sum.  symi_expert_bwd_slots is symi_expert_bwd with one
  * weight gradient per replica SLOT, summed over that slot's own rows only:
  *   dW1_slot [S_tot,2f,d], dW2_slot [S_tot,d,f] f32 out (a slot without rows gets zeros).  */
-int symi_expert_bwd_slots(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
+int symi_expert_bwd_slots(const symi_ctx* ctx, const void* dYp, const void* Xp, const void* UV,
                           const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
                           const void* W1_slots, const void* W2_slots, void* dXp, float* dW1_slot,
                           float* dW2_slot, void* ws, void* stream);
@@ -248,7 +271,7 @@ int symi_expert_bwd_slots(const symi_cfg* cfg, const void* dYp, const void* Xp, 
  * order, the sum is multiplied by `scale` (the paper "normalizes" without stating the
  * divisor: pass 1 for the plain sum, 1/r or 1/N for an average) and copied to all of the
  * class's slots.  In place on dW1_slot [S_tot,2f,d], dW2_slot [S_tot,d,f] f32.          */
-int symi_replica_allreduce(const symi_cfg* cfg, const int32_t* first_slot, float scale,
+int symi_replica_allreduce(const symi_ctx* ctx, const int32_t* first_slot, float scale,
                            float* dW1_slot, float* dW2_slot, void* stream);
 
 /* ---- host helpers for the multi-rank part of the method (no GPU work; all pointers HOST).
@@ -292,17 +315,15 @@ typedef struct {
 } symi_cost_out;
 int symi_comm_cost(const symi_cost_in* in, symi_cost_out* out);
 
-/* Measurement aid (not part of the method): while enabled, every kernel the library
- * launches is bracketed by two HIP events recorded on the launch stream, so that a
- * benchmark can read per-kernel durations of its own timed region.  Enabling it makes
- * calls create events (a host-side allocation); it is off by default.  Kernel ids run
- * from 0 to symi_kernel_count()-1 and have the names symi_kernel_name() returns.
- * symi_timing_read waits for the recorded events of that kernel and returns the summed
- * duration in milliseconds and the number of launches since the last reset.  Host
- * pointers; not thread safe. */
-int symi_timing_enable(int on);
-int symi_timing_reset(void);
-int symi_timing_read(int kernel_id, double* total_ms, int* launches);
+/* Measurement aid (not part of the method): every kernel launched through a context created
+ * with SYMI_CTX_TIMING is bracketed by two HIP events recorded on the launch stream, so that a
+ * benchmark can read per-kernel durations of its own timed region (such a context creates two
+ * events per launch: a host-side allocation).  Kernel ids run from 0 to symi_kernel_count()-1
+ * and have the names symi_kernel_name() returns.  symi_timing_read waits for the recorded
+ * events of that kernel and returns the summed duration in milliseconds and the number of
+ * launches since the last symi_timing_reset.  Host pointers. */
+int symi_timing_reset(const symi_ctx* ctx);
+int symi_timing_read(const symi_ctx* ctx, int kernel_id, double* total_ms, int* launches);
 int symi_kernel_count(void);
 const char* symi_kernel_name(int kernel_id);
 

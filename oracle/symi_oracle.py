@@ -10,8 +10,6 @@ What each function follows
   router_forward, router_backward   Sec. 2.1: the learned gate network (a linear layer)
   route             Sec. 2.1 (top-k gating) and Sec. 3.2 step 1 (per-class token count)
   place             Appendix A.3, Algorithm 1 (Expert Placement Scheduler), Sec. 3.4
-  place_float_literal   the same listing evaluated in binary64 as printed (a second
-                    implementation used as a pin; not normative)
   dispatch          Sec. 3.2 step 2 (tokens of a class are spread over its replicas)
   slot_capacity, dispatch_capacity   Sec. 3.4: capacity(e_i) = slot_capacity * r_i; the
                     assignments of a class beyond its capacity are dropped
@@ -20,7 +18,7 @@ What each function follows
                     where the class gradient is summed, not its value)
   slot_gradients, replica_allreduce   Sec. 4.1 (Fig. 7): per-slot gradients, then
                     add into the representative slot, scale, copy back
-  get_source, collect_grads     App. A.4, Algorithm 2 (gradient collection plan), Sec. 4.3
+  host_table, source_matrix, gradient_plan   App. A.4, Algorithm 2 (gradient collection plan), Sec. 4.3
   rank_group        Sec. 4.2 (groups of consecutive ranks)
   comm_cost         Sec. 3.3 (I)-(III), App. A.5: memory, data volume, communication time
   adam_step, adam_to_replicas   Sec. 3.2 steps 4-8: Adam on the static 1/N shard of
@@ -139,27 +137,6 @@ def place(popularity, S_tot):
     first_slot = np.concatenate([[0], np.cumsum(counts)])
     return (np.array(counts, dtype=np.int32), np.array(placement, dtype=np.int32),
             first_slot.astype(np.int32))
-
-
-def place_float_literal(popularity, S_tot):
-    """The listing of Algorithm 1 evaluated in binary64 exactly as printed."""
-    pop = np.asarray(popularity, dtype=F64)
-    E = len(pop)
-    if pop.sum() == 0:
-        pop = np.ones(E)
-    goal = (pop / pop.sum()) * S_tot
-    counts = np.floor(np.maximum(goal, np.ones(E)))
-    diff = counts - goal
-    while counts.sum() > S_tot:
-        i = int(np.argmax(diff))
-        if counts[i] > 1:
-            counts[i] -= 1
-        diff[i] -= 1
-    while counts.sum() < S_tot:
-        i = int(np.argmin(diff))
-        counts[i] += 1
-        diff[i] += 1
-    return counts.astype(np.int32)
 
 
 # ------------------------------------------------------------------------ dispatch
@@ -431,32 +408,39 @@ def adam_to_replicas(dW1, dW2, master_w, m, v, placement_next, N, n, hp, bf16,
 
 
 # ------------------------------------------------------- multi-rank planning (host side)
-def hosts_of(placement, N, exp_id):
-    """Ranks hosting class exp_id, ascending; slot q lives on rank q // s, s = S_tot / N."""
-    s = len(placement) // N
-    return sorted({q // s for q in range(len(placement)) if int(placement[q]) == exp_id})
+def host_table(placement, N, E):
+    """hosted [E,N] bool: rank r holds at least one replica slot of class e.  Slot q lives on
+    rank q // s, s = S_tot / N (Sec. 4.1: slots are numbered rank by rank)."""
+    pl = np.asarray(placement, dtype=np.int64)
+    s = len(pl) // N
+    hosted = np.zeros((E, N), dtype=bool)
+    hosted[pl, np.arange(len(pl)) // s] = True
+    return hosted
 
 
-def get_source(placement, N, exp_id, rank):
-    """Algorithm 2: the single rank that supplies class exp_id's gradient shard to the
-    optimizer partition on `rank`: that rank itself when it hosts the class, otherwise the
-    hosts take the destinations in turn (host number rank mod #hosts)."""
-    hosts = hosts_of(placement, N, exp_id)
-    if rank in hosts:
-        return rank
-    return hosts[rank % len(hosts)]
-
-
-def collect_grads(placement, N, E, rank):
-    """Algorithm 2: communication tuples of `rank`.  recv[e] = (source, rank) for every class;
-    send[e] = [(dst, dst), ...] for every class hosted on `rank`."""
-    recv = {e: (get_source(placement, N, e, rank), rank) for e in range(E)}
-    send = {}
+def source_matrix(placement, N, E):
+    """App. A.4 (Algorithm 2), Sec. 4.3, for all (class, destination) pairs at once:
+    src[e, r] = the one rank that supplies class e's gradient shard to the optimizer
+    partition on rank r.  A rank that hosts the class serves itself (local first); every other
+    destination r is served by the hosting rank number (r mod #hosts) of the ascending list of
+    hosting ranks, so the hosts share the remote destinations in turn."""
+    hosted = host_table(placement, N, E)
+    dest = np.arange(N)
+    src = np.empty((E, N), dtype=np.int64)
     for e in range(E):
-        if rank not in hosts_of(placement, N, e):
-            continue
-        send[e] = [(dst, dst) for dst in range(N) if get_source(placement, N, e, dst) == rank]
-    return recv, send
+        ranks = np.flatnonzero(hosted[e])
+        src[e] = np.where(hosted[e], dest, ranks[dest % len(ranks)])
+    return src
+
+
+def gradient_plan(placement, N, E, rank):
+    """What `rank` receives and sends in one gradient collection (App. A.4): recv_src [E] =
+    column `rank` of the source matrix; send = {class hosted on rank: ascending destinations
+    whose partition this rank serves} (the partition index equals the destination rank)."""
+    src = source_matrix(placement, N, E)
+    hosted = host_table(placement, N, E)
+    send = {e: np.flatnonzero(src[e] == rank).tolist() for e in range(E) if hosted[e, rank]}
+    return src[:, rank].copy(), send
 
 
 def rank_group(N, first_rank, last_rank):

@@ -125,11 +125,11 @@ __global__ __launch_bounds__(SYMI_ADAM_BLOCK) void adam_to_replicas_kernel(
 
 using namespace symi;
 
-static int adam_impl(const char* who, const symi_cfg* cfg, const symi_adam* hp,
+static int adam_impl(const char* who, const symi_ctx* ctx, const symi_adam* hp,
                      const float* dW1_class, const float* dW2_class, float* master_w, float* m,
                      float* v, const int32_t* slot_offsets, const int32_t* first_slot,
                      const int32_t* first_slot_next, void* W1_slots, void* W2_slots, void* stream) {
-  if (int rc = check_cfg(cfg, who)) return rc;
+  SYMI_ENTER(ctx, who);
   SYMI_REQUIRE(hp && dW1_class && dW2_class && master_w && m && v && first_slot_next && W1_slots &&
                    W2_slots, who, "NULL pointer");
   SYMI_REQUIRE(hp->step >= 1, who, "step must be >= 1");
@@ -151,25 +151,25 @@ static int adam_impl(const char* who, const symi_cfg* cfg, const symi_adam* hp,
   dim3 grid((unsigned)gx, (unsigned)cfg->E);
   hipStream_t st = as_stream(stream);
   if (cfg->dtype == SYMI_BF16)
-    SYMI_TIMED(K_ADAM, st, (adam_to_replicas_kernel<true, SYMI_ADAM_NT, SYMI_ADAM_UNROLL><<<grid, SYMI_ADAM_BLOCK, 0, st>>>(
+    SYMI_TIMED(ctx, K_ADAM, st, (adam_to_replicas_kernel<true, SYMI_ADAM_NT, SYMI_ADAM_UNROLL><<<grid, SYMI_ADAM_BLOCK, 0, st>>>(
         dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s, slot_offsets, first_slot)));
   else
-    SYMI_TIMED(K_ADAM, st, (adam_to_replicas_kernel<false, SYMI_ADAM_NT, SYMI_ADAM_UNROLL><<<grid, SYMI_ADAM_BLOCK, 0, st>>>(
+    SYMI_TIMED(ctx, K_ADAM, st, (adam_to_replicas_kernel<false, SYMI_ADAM_NT, SYMI_ADAM_UNROLL><<<grid, SYMI_ADAM_BLOCK, 0, st>>>(
         dW1_class, dW2_class, master_w, m, v, first_slot_next, W1_slots, W2_slots, n1, n2, per, lo, s, slot_offsets, first_slot)));
   SYMI_LAUNCH_CHECK(who);
   return SYMI_OK;
 }
 
-extern "C" int symi_adam_to_replicas(const symi_cfg* cfg, const symi_adam* hp,
+extern "C" int symi_adam_to_replicas(const symi_ctx* ctx, const symi_adam* hp,
                                      const float* dW1_class, const float* dW2_class,
                                      float* master_w, float* m, float* v,
                                      const int32_t* first_slot_next, void* W1_slots,
                                      void* W2_slots, void* stream) {
-  return adam_impl("symi_adam_to_replicas", cfg, hp, dW1_class, dW2_class, master_w, m, v, nullptr,
+  return adam_impl("symi_adam_to_replicas", ctx, hp, dW1_class, dW2_class, master_w, m, v, nullptr,
                    nullptr, first_slot_next, W1_slots, W2_slots, stream);
 }
 
-extern "C" int symi_adam_to_replicas_active(const symi_cfg* cfg, const symi_adam* hp,
+extern "C" int symi_adam_to_replicas_active(const symi_ctx* ctx, const symi_adam* hp,
                                             const float* dW1_class, const float* dW2_class,
                                             float* master_w, float* m, float* v,
                                             const int32_t* slot_offsets, const int32_t* first_slot,
@@ -179,6 +179,6 @@ extern "C" int symi_adam_to_replicas_active(const symi_cfg* cfg, const symi_adam
     set_error("symi_adam_to_replicas_active: NULL pointer");
     return SYMI_EINVAL;
   }
-  return adam_impl("symi_adam_to_replicas_active", cfg, hp, dW1_class, dW2_class, master_w, m, v,
+  return adam_impl("symi_adam_to_replicas_active", ctx, hp, dW1_class, dW2_class, master_w, m, v,
                    slot_offsets, first_slot, first_slot_next, W1_slots, W2_slots, stream);
 }

@@ -2,6 +2,7 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <new>
 #include <vector>
 
 #include "common.h"
@@ -44,6 +45,21 @@ int check_cfg(const symi_cfg* c, const char* who) {
   BAD((Pe / c->N) % 8, "P_e / N is not a multiple of 8");
   BAD((long long)c->T * c->k > 0x7fffffffLL / 2, "T*k too large for int32 indexing");
 #undef BAD
+#define UNSUPPORTED(cond, msg)           \
+  if (cond) {                            \
+    set_error("%s: %s", who, msg);       \
+    return SYMI_EUNSUPPORTED;            \
+  }
+  // launch limits of the kernels: the m-tile index of the grouped GEMM (one per 64 rows in the
+  // fp32 twin, plus the slices of a cut last round) and the router's 128-token tiles are grid.y
+  // coordinates; the GEMM's per-lane element offsets inside a slot's weights are 32 bits
+  const long long A = (long long)c->T * c->k;
+  const long long mtiles = A / GEMM_BM + c->S_tot;
+  UNSUPPORTED(c->dtype == SYMI_BF16 ? mtiles + 256 > 65535 : 4 * mtiles > 65535,
+              "T*k/256 + S_tot (m-tiles of the grouped GEMM; four times that for fp32) exceeds the grid limit");
+  UNSUPPORTED(((long long)c->T + 127) / 128 > 65535, "T/128 exceeds the grid limit of the router kernels");
+  UNSUPPORTED(2LL * c->f * c->d >= (1LL << 31), "2*f*d must stay below 2^31");
+#undef UNSUPPORTED
   return SYMI_OK;
 }
 
@@ -74,57 +90,155 @@ WsLayout ws_layout(const symi_cfg* c) {
   return L;
 }
 
-// ---- optional per-kernel event timing (off by default; used by the benchmark)
-bool g_timing = false;
-struct TimedLaunch { int kid; hipEvent_t a, b; };
-static std::vector<TimedLaunch> g_launches;
-static hipEvent_t g_open[K_COUNT];
+// ---- optional per-kernel event timing (contexts created with SYMI_CTX_TIMING; used by the
+// benchmark)
 static const char* const g_names[K_COUNT] = {
     "fill_i32", "route", "route_bwd", "place", "chunk_count", "chunk_scan", "chunk_rank",
     "gather_rows", "tile_map", "gemm_fwd1", "gemm_fwd2", "gemm_bwd_dh", "gemm_bwd_dx",
     "gemm_wgrad2", "gemm_wgrad1", "combine", "combine_bwd", "dispatch_bwd", "adam_to_replicas",
     "replica_allreduce", "router_fwd", "router_dx", "router_dw", "slice_sum"};
 
-void timing_begin(int kid, hipStream_t st) {
+void timing_begin(const symi_ctx* ctx, int kid, hipStream_t st) {
   hipEvent_t e;
   if (hipEventCreate(&e) != hipSuccess) return;
   (void)hipEventRecord(e, st);
-  g_open[kid] = e;
+  ctx->open[kid] = e;
 }
-void timing_end(int kid, hipStream_t st) {
+void timing_end(const symi_ctx* ctx, int kid, hipStream_t st) {
   hipEvent_t e;
-  if (!g_open[kid] || hipEventCreate(&e) != hipSuccess) return;
+  if (!ctx->open[kid] || hipEventCreate(&e) != hipSuccess) return;
   (void)hipEventRecord(e, st);
-  g_launches.push_back({kid, g_open[kid], e});
-  g_open[kid] = nullptr;
+  ctx->launches.push_back({kid, ctx->open[kid], e});
+  ctx->open[kid] = nullptr;
+}
+
+int enter(const symi_ctx* ctx, const char* who) {
+  if (!ctx || ctx->magic != CTX_MAGIC) {
+    set_error("%s: ctx is NULL or not a live context of symi_create", who);
+    return SYMI_EINVAL;
+  }
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device) {
+    (void)hipGetLastError();
+    set_error("%s: the context was created on device %d, the current device is %d", who, ctx->device, dev);
+    return SYMI_EINVAL;
+  }
+  return SYMI_OK;
+}
+
+// The expert backward runs its weight-gradient chain on a stream of its own while the products
+// are only a few rounds of workgroups (gemm.hip); larger shapes fill the chip anyway.
+static bool wants_side_stream(const symi_cfg* c, int cus) {
+  const long long A = (long long)c->T * c->k;
+  const long long max_mtiles = A / GEMM_BM + c->S_tot;
+  return A > 0 && max_mtiles * cdiv(c->d, 256) < 8LL * cus;
+}
+
+static void release(symi_ctx* ctx) {
+  for (auto& l : ctx->launches) {
+    (void)hipEventDestroy(l.a);
+    (void)hipEventDestroy(l.b);
+  }
+  ctx->launches.clear();
+  for (auto& e : ctx->open)
+    if (e) { (void)hipEventDestroy(e); e = nullptr; }
+  if (ctx->fork) (void)hipEventDestroy(ctx->fork);
+  if (ctx->mid) (void)hipEventDestroy(ctx->mid);
+  if (ctx->join) (void)hipEventDestroy(ctx->join);
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
+  ctx->fork = ctx->mid = ctx->join = nullptr;
+  ctx->side = nullptr;
 }
 
 }  // namespace symi
 
 extern "C" {
 
-int symi_timing_enable(int on) {
-  symi::g_timing = on != 0;
+int symi_create(const symi_cfg* cfg, unsigned flags, symi_ctx** out) {
+  if (!out) {
+    symi::set_error("symi_create: out is NULL");
+    return SYMI_EINVAL;
+  }
+  *out = nullptr;
+  if (int rc = symi::check_cfg(cfg, "symi_create")) return rc;
+  if (flags & ~(unsigned)(SYMI_CTX_NO_OVERLAP | SYMI_CTX_NO_SLICING | SYMI_CTX_TIMING)) {
+    symi::set_error("symi_create: unknown flag bits 0x%x", flags);
+    return SYMI_EINVAL;
+  }
+  int dev = -1, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+    (void)hipGetLastError();
+    symi::set_error("symi_create: no usable HIP device is current");
+    return SYMI_EHIP;
+  }
+  symi_ctx* ctx = new (std::nothrow) symi_ctx();
+  if (!ctx) {
+    symi::set_error("symi_create: out of host memory");
+    return SYMI_EHIP;
+  }
+  ctx->cfg = *cfg;
+  ctx->flags = flags;
+  ctx->device = dev;
+  ctx->cus = cus;
+  ctx->L = symi::ws_layout(cfg);
+  ctx->overlap = !(flags & SYMI_CTX_NO_OVERLAP);
+  ctx->slicing = !(flags & SYMI_CTX_NO_SLICING);
+  ctx->timing = (flags & SYMI_CTX_TIMING) != 0;
+  ctx->side = nullptr;
+  ctx->fork = ctx->mid = ctx->join = nullptr;
+  for (auto& e : ctx->open) e = nullptr;
+  if (ctx->overlap && symi::wants_side_stream(cfg, cus)) {
+    // default priority, non-blocking with respect to the NULL stream
+    const bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess &&
+                    hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming) == hipSuccess &&
+                    hipEventCreateWithFlags(&ctx->mid, hipEventDisableTiming) == hipSuccess &&
+                    hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+      symi::set_error("symi_create: creating the helper stream failed: %s", hipGetErrorString(hipGetLastError()));
+      symi::release(ctx);
+      delete ctx;
+      return SYMI_EHIP;
+    }
+  }
+  ctx->magic = symi::CTX_MAGIC;
+  *out = ctx;
   return SYMI_OK;
 }
 
-int symi_timing_reset(void) {
-  for (auto& l : symi::g_launches) {
+int symi_destroy(symi_ctx* ctx) {
+  if (!ctx) return SYMI_OK;
+  if (ctx->magic != symi::CTX_MAGIC) {
+    symi::set_error("symi_destroy: not a live context of symi_create");
+    return SYMI_EINVAL;
+  }
+  ctx->magic = 0;
+  symi::release(ctx);
+  delete ctx;
+  return SYMI_OK;
+}
+
+int symi_timing_reset(const symi_ctx* ctx) {
+  if (!ctx || ctx->magic != symi::CTX_MAGIC) {
+    symi::set_error("symi_timing_reset: bad context");
+    return SYMI_EINVAL;
+  }
+  for (auto& l : ctx->launches) {
     (void)hipEventDestroy(l.a);
     (void)hipEventDestroy(l.b);
   }
-  symi::g_launches.clear();
+  ctx->launches.clear();
   return SYMI_OK;
 }
 
-int symi_timing_read(int kernel_id, double* total_ms, int* launches) {
-  if (kernel_id < 0 || kernel_id >= symi::K_COUNT || !total_ms || !launches) {
+int symi_timing_read(const symi_ctx* ctx, int kernel_id, double* total_ms, int* launches) {
+  if (!ctx || ctx->magic != symi::CTX_MAGIC || kernel_id < 0 || kernel_id >= symi::K_COUNT || !total_ms || !launches) {
     symi::set_error("symi_timing_read: bad argument");
     return SYMI_EINVAL;
   }
   double tot = 0.0;
   int n = 0;
-  for (auto& l : symi::g_launches) {
+  for (auto& l : ctx->launches) {
     if (l.kid != kernel_id) continue;
     if (hipEventSynchronize(l.b) != hipSuccess) {
       symi::set_error("symi_timing_read: hipEventSynchronize failed");

@@ -4,13 +4,14 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <vector>
+
 #include "symi.h"
 
 namespace symi {
 
 void set_error(const char* fmt, ...);
 int check_cfg(const symi_cfg* cfg, const char* who);
-void launch_fill_i32(int32_t* p, int n, int32_t val, hipStream_t st);
 
 // Kernel ids for the optional event timing (symi_timing_*).
 enum KernelId {
@@ -18,17 +19,7 @@ enum KernelId {
   K_TILE_MAP, K_GEMM_FWD1, K_GEMM_FWD2, K_GEMM_BWD_DH, K_GEMM_BWD_DX, K_GEMM_WGRAD2, K_GEMM_WGRAD1,
   K_COMBINE, K_COMBINE_BWD, K_DISPATCH_BWD, K_ADAM, K_REPLICA_AR, K_ROUTER_FWD, K_ROUTER_DX, K_ROUTER_DW, K_SLICE_SUM, K_COUNT
 };
-extern bool g_timing;
-void timing_begin(int kid, hipStream_t st);
-void timing_end(int kid, hipStream_t st);
-
-// Brackets one kernel launch with events when timing is on; otherwise just launches.
-#define SYMI_TIMED(kid, st, launch)            \
-  do {                                         \
-    if (symi::g_timing) symi::timing_begin(kid, st); \
-    launch;                                    \
-    if (symi::g_timing) symi::timing_end(kid, st);   \
-  } while (0)
+struct TimedLaunch { int kid; hipEvent_t a, b; };
 
 #define SYMI_REQUIRE(cond, who, msg)                      \
   do {                                                    \
@@ -46,6 +37,11 @@ void timing_end(int kid, hipStream_t st);
       return SYMI_EHIP;                                                   \
     }                                                                     \
   } while (0)
+
+// Every device call starts with this: checks the context, makes `cfg` its configuration.
+#define SYMI_ENTER(ctx, who)                               \
+  if (int rc_enter_ = symi::enter(ctx, who)) return rc_enter_; \
+  const symi_cfg* const cfg = &(ctx)->cfg
 
 static inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -90,3 +86,38 @@ constexpr int SPLIT_CUS = 256;        // compute units the slicing fills (at mos
 constexpr size_t SPLIT_TILE_BYTES = 256 * 256 * sizeof(float);
 
 }  // namespace symi
+
+// The opaque context of include/symi.h: the validated configuration plus everything the
+// library owns for it.  Created and destroyed by symi_create / symi_destroy; the hot calls
+// only read it (the event list of the optional timing is the one thing they append to).
+struct symi_ctx {
+  uint32_t magic;
+  symi_cfg cfg;
+  unsigned flags;
+  int device;            // the device that was current in symi_create
+  int cus;               // its compute units
+  symi::WsLayout L;      // layout of the caller's workspace for cfg
+  bool overlap, slicing, timing;
+  // helper stream of the expert backward with its fork / hand-over / join events
+  // (nullptr when the flags or the shape rule it out)
+  hipStream_t side;
+  hipEvent_t fork, mid, join;
+  mutable std::vector<symi::TimedLaunch> launches;
+  mutable hipEvent_t open[symi::K_COUNT];
+};
+
+namespace symi {
+constexpr uint32_t CTX_MAGIC = 0x53594d49u;   // "SYMI"
+int enter(const symi_ctx* ctx, const char* who);
+void timing_begin(const symi_ctx* ctx, int kid, hipStream_t st);
+void timing_end(const symi_ctx* ctx, int kid, hipStream_t st);
+void launch_fill_i32(const symi_ctx* ctx, int32_t* p, int n, int32_t val, hipStream_t st);
+}  // namespace symi
+
+// Brackets one kernel launch with events when the context was created with SYMI_CTX_TIMING.
+#define SYMI_TIMED(ctx, kid, st, launch)                      \
+  do {                                                        \
+    if ((ctx)->timing) symi::timing_begin(ctx, kid, st);      \
+    launch;                                                   \
+    if ((ctx)->timing) symi::timing_end(ctx, kid, st);        \
+  } while (0)

@@ -294,41 +294,41 @@ static int grid_for(long long work_items, int per_block) {
 
 using namespace symi;
 
-static int dispatch_impl(const char* who, const symi_cfg* cfg, int slot_cap, const void* X,
+static int dispatch_impl(const char* who, const symi_ctx* ctx, int slot_cap, const void* X,
                          const int32_t* idx, const int32_t* hist, const int32_t* counts,
                          const int32_t* first_slot, int32_t* row_of_assign, int32_t* assign_of_row,
                          int32_t* slot_offsets, void* Xp, void* ws, void* stream) {
-  if (int rc = check_cfg(cfg, who)) return rc;
+  SYMI_ENTER(ctx, who);
   SYMI_REQUIRE(hist && counts && first_slot && slot_offsets && ws, who, "NULL pointer");
   SYMI_REQUIRE(cfg->T == 0 || (X && idx && row_of_assign && assign_of_row && Xp), who, "NULL pointer");
   hipStream_t st = as_stream(stream);
   const int E = cfg->E, A = cfg->T * cfg->k;
-  const WsLayout L = ws_layout(cfg);
+  const WsLayout& L = ctx->L;
   int32_t* blk = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.blk_counts);
   int32_t* tab = slot_cap > 0 ? reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.class_tab) : nullptr;
   const int nblk = cdiv(A, DISPATCH_CHUNK);
   if (nblk > 0)
-    SYMI_TIMED(K_CHUNK_COUNT, st, (chunk_count_kernel<<<nblk, DT, E * sizeof(int32_t), st>>>(idx, A, E, blk)));
-  SYMI_TIMED(K_CHUNK_SCAN, st, (chunk_scan_kernel<<<E, DT, 0, st>>>(blk, nblk, E, cfg->S_tot, A, hist, counts,
+    SYMI_TIMED(ctx, K_CHUNK_COUNT, st, (chunk_count_kernel<<<nblk, DT, E * sizeof(int32_t), st>>>(idx, A, E, blk)));
+  SYMI_TIMED(ctx, K_CHUNK_SCAN, st, (chunk_scan_kernel<<<E, DT, 0, st>>>(blk, nblk, E, cfg->S_tot, A, hist, counts,
                                                                     first_slot, slot_offsets, slot_cap, tab)));
   if (nblk > 0) {
-    SYMI_TIMED(K_CHUNK_RANK, st, (chunk_rank_kernel<<<nblk, DT, (size_t)(1 + DT / 64) * E * sizeof(int32_t), st>>>(
+    SYMI_TIMED(ctx, K_CHUNK_RANK, st, (chunk_rank_kernel<<<nblk, DT, (size_t)(1 + DT / 64) * E * sizeof(int32_t), st>>>(
         idx, A, E, blk, row_of_assign, assign_of_row, tab)));
     const int w = cfg->dtype == SYMI_BF16 ? 2 : 4;
     const int vpr = cfg->d * w / 16;
     const long long nvec = (long long)cfg->T * vpr;
-    SYMI_TIMED(K_GATHER, st, (scatter_rows_kernel<<<grid_for(nvec, 256 * 2), 256, 0, st>>>(
+    SYMI_TIMED(ctx, K_GATHER, st, (scatter_rows_kernel<<<grid_for(nvec, 256 * 2), 256, 0, st>>>(
         static_cast<const uint4*>(X), static_cast<uint4*>(Xp), row_of_assign, cfg->k, nvec, vpr)));
   }
   SYMI_LAUNCH_CHECK(who);
   return SYMI_OK;
 }
 
-extern "C" int symi_dispatch(const symi_cfg* cfg, const void* X, const int32_t* idx,
+extern "C" int symi_dispatch(const symi_ctx* ctx, const void* X, const int32_t* idx,
                              const int32_t* hist, const int32_t* counts, const int32_t* first_slot,
                              int32_t* row_of_assign, int32_t* assign_of_row, int32_t* slot_offsets,
                              void* Xp, void* ws, void* stream) {
-  return dispatch_impl("symi_dispatch", cfg, 0, X, idx, hist, counts, first_slot, row_of_assign,
+  return dispatch_impl("symi_dispatch", ctx, 0, X, idx, hist, counts, first_slot, row_of_assign,
                        assign_of_row, slot_offsets, Xp, ws, stream);
 }
 
@@ -345,67 +345,66 @@ extern "C" int symi_slot_capacity(const symi_cfg* cfg, double capacity_factor) {
   return (int)c;
 }
 
-extern "C" int symi_dispatch_capacity(const symi_cfg* cfg, int slot_capacity, const void* X,
+extern "C" int symi_dispatch_capacity(const symi_ctx* ctx, int slot_capacity, const void* X,
                                       const int32_t* idx, const int32_t* hist, const int32_t* counts,
                                       const int32_t* first_slot, int32_t* row_of_assign,
                                       int32_t* assign_of_row, int32_t* slot_offsets, void* Xp,
                                       void* ws, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_dispatch_capacity")) return rc;
   SYMI_REQUIRE(slot_capacity >= 1, "symi_dispatch_capacity", "slot_capacity must be >= 1");
-  return dispatch_impl("symi_dispatch_capacity", cfg, slot_capacity, X, idx, hist, counts, first_slot,
+  return dispatch_impl("symi_dispatch_capacity", ctx, slot_capacity, X, idx, hist, counts, first_slot,
                        row_of_assign, assign_of_row, slot_offsets, Xp, ws, stream);
 }
 
-extern "C" int symi_dispatch_bwd(const symi_cfg* cfg, const void* dXp, const int32_t* row_of_assign,
+extern "C" int symi_dispatch_bwd(const symi_ctx* ctx, const void* dXp, const int32_t* row_of_assign,
                                  void* dX, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_dispatch_bwd")) return rc;
+  SYMI_ENTER(ctx, "symi_dispatch_bwd");
   if (cfg->T == 0) return SYMI_OK;
   SYMI_REQUIRE(dXp && row_of_assign && dX, "symi_dispatch_bwd", "NULL pointer");
   hipStream_t st = as_stream(stream);
   if (cfg->dtype == SYMI_BF16) {
     const int ppr = cfg->d / 8;
-    SYMI_TIMED(K_DISPATCH_BWD, st, (combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+    SYMI_TIMED(ctx, K_DISPATCH_BWD, st, (combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
         dXp, row_of_assign, nullptr, dX, cfg->T, cfg->k, ppr)));
   } else {
     const int ppr = cfg->d / 4;
-    SYMI_TIMED(K_DISPATCH_BWD, st, (combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+    SYMI_TIMED(ctx, K_DISPATCH_BWD, st, (combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
         dXp, row_of_assign, nullptr, dX, cfg->T, cfg->k, ppr)));
   }
   SYMI_LAUNCH_CHECK("symi_dispatch_bwd");
   return SYMI_OK;
 }
 
-extern "C" int symi_combine(const symi_cfg* cfg, const void* Yp, const int32_t* row_of_assign,
+extern "C" int symi_combine(const symi_ctx* ctx, const void* Yp, const int32_t* row_of_assign,
                             const float* gate, void* Y, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_combine")) return rc;
+  SYMI_ENTER(ctx, "symi_combine");
   if (cfg->T == 0) return SYMI_OK;
   SYMI_REQUIRE(Yp && row_of_assign && gate && Y, "symi_combine", "NULL pointer");
   hipStream_t st = as_stream(stream);
   if (cfg->dtype == SYMI_BF16) {
     const int ppr = cfg->d / 8;
-    SYMI_TIMED(K_COMBINE, st, (combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+    SYMI_TIMED(ctx, K_COMBINE, st, (combine_kernel<true><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
         Yp, row_of_assign, gate, Y, cfg->T, cfg->k, ppr)));
   } else {
     const int ppr = cfg->d / 4;
-    SYMI_TIMED(K_COMBINE, st, (combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
+    SYMI_TIMED(ctx, K_COMBINE, st, (combine_kernel<false><<<grid_for((long long)cfg->T * ppr, 256), 256, 0, st>>>(
         Yp, row_of_assign, gate, Y, cfg->T, cfg->k, ppr)));
   }
   SYMI_LAUNCH_CHECK("symi_combine");
   return SYMI_OK;
 }
 
-extern "C" int symi_combine_bwd(const symi_cfg* cfg, const void* dY, const void* Yp,
+extern "C" int symi_combine_bwd(const symi_ctx* ctx, const void* dY, const void* Yp,
                                 const int32_t* row_of_assign, const float* gate, void* dYp,
                                 float* dgate, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_combine_bwd")) return rc;
+  SYMI_ENTER(ctx, "symi_combine_bwd");
   if (cfg->T == 0) return SYMI_OK;
   SYMI_REQUIRE(dY && Yp && row_of_assign && gate && dYp && dgate, "symi_combine_bwd", "NULL pointer");
   hipStream_t st = as_stream(stream);
   if (cfg->dtype == SYMI_BF16)
-    SYMI_TIMED(K_COMBINE_BWD, st, (combine_bwd_kernel<true><<<grid_for(cfg->T, 4), 256, 0, st>>>(
+    SYMI_TIMED(ctx, K_COMBINE_BWD, st, (combine_bwd_kernel<true><<<grid_for(cfg->T, 4), 256, 0, st>>>(
         dY, Yp, row_of_assign, gate, dYp, dgate, cfg->T, cfg->k, cfg->d / 8)));
   else
-    SYMI_TIMED(K_COMBINE_BWD, st, (combine_bwd_kernel<false><<<grid_for(cfg->T, 4), 256, 0, st>>>(
+    SYMI_TIMED(ctx, K_COMBINE_BWD, st, (combine_bwd_kernel<false><<<grid_for(cfg->T, 4), 256, 0, st>>>(
         dY, Yp, row_of_assign, gate, dYp, dgate, cfg->T, cfg->k, cfg->d / 4)));
   SYMI_LAUNCH_CHECK("symi_combine_bwd");
   return SYMI_OK;

@@ -849,8 +849,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
 }
 
 template <int MODE>
-static void launch_gemm(const symi_cfg* cfg, const GemmParams& p, int n_cols, int max_mtiles,
+static void launch_gemm(const symi_ctx* ctx, const GemmParams& p, int n_cols, int max_mtiles,
                         hipStream_t st) {
+  const symi_cfg* const cfg = &ctx->cfg;
   if (cfg->dtype == SYMI_BF16) {
     const int bn = MODE == FWD1 ? BN / 2 : BN;
     const int ntx = cdiv(n_cols, bn);
@@ -858,70 +859,56 @@ static void launch_gemm(const symi_cfg* cfg, const GemmParams& p, int n_cols, in
     const bool may_slice = (MODE == FWD2 || MODE == BWD_DX) && p.partials && cdiv(p.K, BK) / 16 >= 2;
     const int extra = may_slice ? cdiv(p.cus, ntx) : 0;
     dim3 grid(ntx, MODE <= BWD_DX ? max_mtiles + extra : cdiv(p.M, BM), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
-    SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_bf16_kernel<MODE><<<grid, GT, 0, st>>>(p)));
+    SYMI_TIMED(ctx, K_GEMM_FWD1 + MODE, st, (gemm_bf16_kernel<MODE><<<grid, GT, 0, st>>>(p)));
     if (may_slice)   // the sliced round holds at most cus / 2 tiles
-      SYMI_TIMED(K_SLICE_SUM, st, (slice_sum_kernel<<<dim3(BM / 16, std::max(1, p.cus / 2)), 256, 0, st>>>(p, ntx)));
+      SYMI_TIMED(ctx, K_SLICE_SUM, st, (slice_sum_kernel<<<dim3(BM / 16, std::max(1, p.cus / 2)), 256, 0, st>>>(p, ntx)));
   } else {
     const int bn = MODE == FWD1 ? FB / 2 : FB;
     dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 4 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
-    SYMI_TIMED(K_GEMM_FWD1 + MODE, st, (gemm_f32_kernel<MODE><<<grid, 256, 0, st>>>(p)));
+    SYMI_TIMED(ctx, K_GEMM_FWD1 + MODE, st, (gemm_f32_kernel<MODE><<<grid, 256, 0, st>>>(p)));
   }
-}
-
-// compute units of the current device
-static int device_cus() {
-  static int cus[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cus[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-    cus[dev] = n;
-  }
-  return cus[dev];
 }
 
 // where sliced reductions keep their partial tiles (bf16 configurations only)
-static bool g_slicing = true;
-static void set_split(const symi_cfg* cfg, void* ws, const WsLayout& L, GemmParams& p) {
-  p.cus = std::min(device_cus(), SPLIT_CUS);
-  p.partials = g_slicing && cfg->dtype == SYMI_BF16
-                   ? reinterpret_cast<float*>(static_cast<char*>(ws) + L.split_part) : nullptr;
+static void set_split(const symi_ctx* ctx, void* ws, GemmParams& p) {
+  p.cus = std::min(ctx->cus, SPLIT_CUS);
+  p.partials = ctx->slicing && ctx->cfg.dtype == SYMI_BF16
+                   ? reinterpret_cast<float*>(static_cast<char*>(ws) + ctx->L.split_part) : nullptr;
 }
 
 }  // namespace symi
 
 using namespace symi;
 
-extern "C" int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_t* slot_offsets,
+extern "C" int symi_expert_fwd(const symi_ctx* ctx, const void* Xp, const int32_t* slot_offsets,
                                const void* W1_slots, const void* W2_slots, void* UV, void* H,
                                void* Yp, void* ws, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_expert_fwd")) return rc;
+  SYMI_ENTER(ctx, "symi_expert_fwd");
   const long long A = (long long)cfg->T * cfg->k;
   if (A == 0) return SYMI_OK;
   SYMI_REQUIRE(Xp && slot_offsets && W1_slots && W2_slots && UV && H && Yp && ws, "symi_expert_fwd",
                "NULL pointer");
   hipStream_t st = as_stream(stream);
-  const WsLayout L = ws_layout(cfg);
+  const WsLayout& L = ctx->L;
   int32_t* map = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.tile_map);
   const int max_mtiles = (int)(A / GEMM_BM) + cfg->S_tot;
-  SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, nullptr, cfg->S_tot, cfg->E, map, nullptr)));
+  SYMI_TIMED(ctx, K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, nullptr, cfg->S_tot, cfg->E, map, nullptr)));
 
   GemmParams p = {};
   p.tile_map = map;
-  set_split(cfg, ws, L, p);
+  set_split(ctx, ws, p);
   p.d = cfg->d;
   p.f = cfg->f;
   // u|v = Xp W1^T, h = silu(u)*v
   p.A = Xp; p.B = W1_slots; p.UVout = UV; p.H = H;
   p.b_group_stride = 2LL * cfg->f * cfg->d;
   p.N = cfg->f; p.K = cfg->d;
-  launch_gemm<FWD1>(cfg, p, cfg->f, max_mtiles, st);
+  launch_gemm<FWD1>(ctx, p, cfg->f, max_mtiles, st);
   // Yp = h W2^T
   p.A = H; p.B = W2_slots; p.C = Yp;
   p.b_group_stride = (long long)cfg->d * cfg->f;
   p.N = cfg->d; p.K = cfg->f;
-  launch_gemm<FWD2>(cfg, p, cfg->d, max_mtiles, st);
+  launch_gemm<FWD2>(ctx, p, cfg->d, max_mtiles, st);
   SYMI_LAUNCH_CHECK("symi_expert_fwd");
   return SYMI_OK;
 }
@@ -931,46 +918,25 @@ extern "C" int symi_expert_fwd(const symi_cfg* cfg, const void* Xp, const int32_
 // Run back to back each launch rounds its tile count up to whole rounds of 256 workgroups
 // (config c2: 296 tiles of the dXp product are two rounds, the second one 84 % empty) and
 // the store-bound zero tiles of the weight gradients never meet the MFMA-bound tiles.  The
-// second chain is therefore enqueued on a helper stream (one per device, created at the
-// first call, default priority, non-blocking) forked from and joined back into the caller's
-// stream with events, so workgroups of both chains share the chip.  This is done when the
-// dXp product has fewer than 8 rounds of tiles; symi_set_overlap(0) turns it off altogether
-// (everything on the caller's stream, in order).
-struct SideStream {
-  hipStream_t s = nullptr;
-  hipEvent_t fork = nullptr, mid = nullptr, join = nullptr;
-  bool ok = false, tried = false;
-};
-static bool g_overlap = true;
-static SideStream* side_stream() {
-  static SideStream side[64];
-  int dev = 0;
-  if (!g_overlap || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-  SideStream& x = side[dev];
-  if (!x.tried) {
-    x.tried = true;
-    x.ok = hipStreamCreateWithFlags(&x.s, hipStreamNonBlocking) == hipSuccess &&
-           hipEventCreateWithFlags(&x.fork, hipEventDisableTiming) == hipSuccess &&
-           hipEventCreateWithFlags(&x.mid, hipEventDisableTiming) == hipSuccess &&
-           hipEventCreateWithFlags(&x.join, hipEventDisableTiming) == hipSuccess;
-    if (!x.ok) (void)hipGetLastError();
-  }
-  return x.ok ? &x : nullptr;
-}
+// second chain is therefore enqueued on the context's helper stream (created by symi_create
+// when the flags allow it and the dXp product has fewer than 8 rounds of tiles; default
+// priority, non-blocking), forked from and joined back into the caller's stream with events,
+// so workgroups of both chains share the chip.  Otherwise everything stays on the caller's
+// stream, in order.
 
 // per_slot = false: dW1_out / dW2_out are per class (all replica slots summed in the GEMM);
 // per_slot = true: one gradient per replica slot (its own rows only)
-static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp, const void* Xp,
+static int expert_bwd_impl(const char* who, const symi_ctx* ctx, const void* dYp, const void* Xp,
                            const void* UV, const void* H, const int32_t* slot_offsets,
                            const int32_t* first_slot, const void* W1_slots, const void* W2_slots,
                            void* dXp, float* dW1_class, float* dW2_class, void* ws, void* stream,
                            bool per_slot, bool skip_empty = false) {
-  if (int rc = check_cfg(cfg, who)) return rc;
+  SYMI_ENTER(ctx, who);
   const long long A = (long long)cfg->T * cfg->k;
   SYMI_REQUIRE(slot_offsets && first_slot && dW1_class && dW2_class && ws, who, "NULL pointer");
   SYMI_REQUIRE(A == 0 || (dYp && Xp && UV && H && W1_slots && W2_slots && dXp), who, "NULL pointer");
   hipStream_t st = as_stream(stream);
-  const WsLayout L = ws_layout(cfg);
+  const WsLayout& L = ctx->L;
   int32_t* map = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.tile_map);
   void* dUV = static_cast<char*>(ws) + L.duv;
   const int max_mtiles = (int)(A / GEMM_BM) + cfg->S_tot;
@@ -983,34 +949,36 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
   p.class_order = order;
   p.per_slot = per_slot ? 1 : 0;
   p.skip_empty = skip_empty ? 1 : 0;
-  set_split(cfg, ws, L, p);
+  set_split(ctx, ws, p);
   p.d = cfg->d;
   p.f = cfg->f;
-  SYMI_TIMED(K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, first_slot, cfg->S_tot, cfg->E, map, order)));
+  SYMI_TIMED(ctx, K_TILE_MAP, st, (tile_map_kernel<<<1, 256, 0, st>>>(slot_offsets, first_slot, cfg->S_tot, cfg->E, map, order)));
   // worth it only while a product is a few rounds of workgroups: with many rounds the chip is
-  // full anyway and two kernels sharing it only disturb each other's L2 locality
-  const bool few_rounds = (long long)max_mtiles * cdiv(cfg->d, BN) < 8LL * device_cus();
-  SideStream* side = A > 0 && few_rounds ? side_stream() : nullptr;
+  // full anyway and two kernels sharing it only disturb each other's L2 locality (symi_create
+  // decides; the context then holds the helper stream)
+  const bool side = ctx->side != nullptr && A > 0;
   hipStream_t sw = st;   // stream of the weight-gradient chain
   if (side) {
-    bool ok = hipEventRecord(side->fork, st) == hipSuccess &&
-              hipStreamWaitEvent(side->s, side->fork, 0) == hipSuccess;
-    if (ok) sw = side->s; else { side = nullptr; (void)hipGetLastError(); }
+    if (hipEventRecord(ctx->fork, st) != hipSuccess || hipStreamWaitEvent(ctx->side, ctx->fork, 0) != hipSuccess) {
+      set_error("%s: forking onto the helper stream failed", who);
+      return SYMI_EHIP;
+    }
+    sw = ctx->side;
   }
   // class gradients, first half (classes without rows get zeros: their reduction is empty)
   GemmParams pw = p;
   pw.A = dYp; pw.B = H; pw.C = dW2_class;
   pw.c_group_stride = (long long)cfg->d * cfg->f;
   pw.M = cfg->d; pw.N = cfg->f;
-  launch_gemm<WGRAD2>(cfg, pw, cfg->f, 0, sw);
+  launch_gemm<WGRAD2>(ctx, pw, cfg->f, 0, sw);
   if (A > 0) {
     // dh = dYp W2, turned into du, dv in the epilogue (dh itself never reaches memory)
     p.A = dYp; p.B = W2_slots; p.C = dUV; p.UV = UV;
     p.b_group_stride = (long long)cfg->d * cfg->f;
     p.N = cfg->f; p.K = cfg->d;
-    launch_gemm<BWD_DH>(cfg, p, cfg->f, max_mtiles, st);
+    launch_gemm<BWD_DH>(ctx, p, cfg->f, max_mtiles, st);
     if (side) {   // du|dv is complete: the other chain may go on to dW1
-      if (hipEventRecord(side->mid, st) != hipSuccess || hipStreamWaitEvent(side->s, side->mid, 0) != hipSuccess) {
+      if (hipEventRecord(ctx->mid, st) != hipSuccess || hipStreamWaitEvent(ctx->side, ctx->mid, 0) != hipSuccess) {
         set_error("%s: event hand-over between the two streams failed", who);
         return SYMI_EHIP;
       }
@@ -1019,14 +987,14 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
     p.A = dUV; p.B = W1_slots; p.C = dXp;
     p.b_group_stride = 2LL * cfg->f * cfg->d;
     p.N = cfg->d; p.K = 2 * cfg->f;
-    launch_gemm<BWD_DX>(cfg, p, cfg->d, max_mtiles, st);
+    launch_gemm<BWD_DX>(ctx, p, cfg->d, max_mtiles, st);
   }
   pw.A = dUV; pw.B = Xp; pw.C = dW1_class;
   pw.c_group_stride = 2LL * cfg->f * cfg->d;
   pw.M = 2 * cfg->f; pw.N = cfg->d;
-  launch_gemm<WGRAD1>(cfg, pw, cfg->d, 0, sw);
+  launch_gemm<WGRAD1>(ctx, pw, cfg->d, 0, sw);
   if (side) {
-    if (hipEventRecord(side->join, side->s) != hipSuccess || hipStreamWaitEvent(st, side->join, 0) != hipSuccess) {
+    if (hipEventRecord(ctx->join, ctx->side) != hipSuccess || hipStreamWaitEvent(st, ctx->join, 0) != hipSuccess) {
       set_error("%s: joining the helper stream failed", who);
       return SYMI_EHIP;
     }
@@ -1035,39 +1003,29 @@ static int expert_bwd_impl(const char* who, const symi_cfg* cfg, const void* dYp
   return SYMI_OK;
 }
 
-extern "C" int symi_set_slicing(int on) {
-  g_slicing = on != 0;
-  return SYMI_OK;
-}
-
-extern "C" int symi_set_overlap(int on) {
-  g_overlap = on != 0;
-  return SYMI_OK;
-}
-
-extern "C" int symi_expert_bwd(const symi_cfg* cfg, const void* dYp, const void* Xp, const void* UV,
+extern "C" int symi_expert_bwd(const symi_ctx* ctx, const void* dYp, const void* Xp, const void* UV,
                                const void* H, const int32_t* slot_offsets, const int32_t* first_slot,
                                const void* W1_slots, const void* W2_slots, void* dXp,
                                float* dW1_class, float* dW2_class, void* ws, void* stream) {
-  return expert_bwd_impl("symi_expert_bwd", cfg, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots,
+  return expert_bwd_impl("symi_expert_bwd", ctx, dYp, Xp, UV, H, slot_offsets, first_slot, W1_slots,
                          W2_slots, dXp, dW1_class, dW2_class, ws, stream, false);
 }
 
-extern "C" int symi_expert_bwd_active(const symi_cfg* cfg, const void* dYp, const void* Xp,
+extern "C" int symi_expert_bwd_active(const symi_ctx* ctx, const void* dYp, const void* Xp,
                                       const void* UV, const void* H, const int32_t* slot_offsets,
                                       const int32_t* first_slot, const void* W1_slots,
                                       const void* W2_slots, void* dXp, float* dW1_class,
                                       float* dW2_class, void* ws, void* stream) {
-  return expert_bwd_impl("symi_expert_bwd_active", cfg, dYp, Xp, UV, H, slot_offsets, first_slot,
+  return expert_bwd_impl("symi_expert_bwd_active", ctx, dYp, Xp, UV, H, slot_offsets, first_slot,
                          W1_slots, W2_slots, dXp, dW1_class, dW2_class, ws, stream, false, true);
 }
 
-extern "C" int symi_expert_bwd_slots(const symi_cfg* cfg, const void* dYp, const void* Xp,
+extern "C" int symi_expert_bwd_slots(const symi_ctx* ctx, const void* dYp, const void* Xp,
                                      const void* UV, const void* H, const int32_t* slot_offsets,
                                      const int32_t* first_slot, const void* W1_slots,
                                      const void* W2_slots, void* dXp, float* dW1_slot,
                                      float* dW2_slot, void* ws, void* stream) {
-  return expert_bwd_impl("symi_expert_bwd_slots", cfg, dYp, Xp, UV, H, slot_offsets, first_slot,
+  return expert_bwd_impl("symi_expert_bwd_slots", ctx, dYp, Xp, UV, H, slot_offsets, first_slot,
                          W1_slots, W2_slots, dXp, dW1_slot, dW2_slot, ws, stream, true);
 }
 
@@ -1094,16 +1052,16 @@ __global__ __launch_bounds__(256) void replica_allreduce_kernel(float4* __restri
 }
 }  // namespace symi
 
-extern "C" int symi_replica_allreduce(const symi_cfg* cfg, const int32_t* first_slot, float scale,
+extern "C" int symi_replica_allreduce(const symi_ctx* ctx, const int32_t* first_slot, float scale,
                                       float* dW1_slot, float* dW2_slot, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_replica_allreduce")) return rc;
+  SYMI_ENTER(ctx, "symi_replica_allreduce");
   SYMI_REQUIRE(first_slot && dW1_slot && dW2_slot, "symi_replica_allreduce", "NULL pointer");
   hipStream_t st = as_stream(stream);
   const long long n1 = 2LL * cfg->f * cfg->d / 4, n2 = (long long)cfg->d * cfg->f / 4;
   auto blocks = [](long long n4) { long long b = (n4 + 255) / 256; return (unsigned)(b > 2048 ? 2048 : (b < 1 ? 1 : b)); };
-  SYMI_TIMED(K_REPLICA_AR, st, (replica_allreduce_kernel<<<dim3(blocks(n1), cfg->E), 256, 0, st>>>(
+  SYMI_TIMED(ctx, K_REPLICA_AR, st, (replica_allreduce_kernel<<<dim3(blocks(n1), cfg->E), 256, 0, st>>>(
       reinterpret_cast<float4*>(dW1_slot), first_slot, n1, scale)));
-  SYMI_TIMED(K_REPLICA_AR, st, (replica_allreduce_kernel<<<dim3(blocks(n2), cfg->E), 256, 0, st>>>(
+  SYMI_TIMED(ctx, K_REPLICA_AR, st, (replica_allreduce_kernel<<<dim3(blocks(n2), cfg->E), 256, 0, st>>>(
       reinterpret_cast<float4*>(dW2_slot), first_slot, n2, scale)));
   SYMI_LAUNCH_CHECK("symi_replica_allreduce");
   return SYMI_OK;

@@ -204,20 +204,20 @@ static void place_host(const int32_t* pop_in, int E, int S, int32_t* counts, int
 
 using namespace symi;
 
-extern "C" int symi_place(const symi_cfg* cfg, const int32_t* popularity, int32_t* counts,
+extern "C" int symi_place(const symi_ctx* ctx, const int32_t* popularity, int32_t* counts,
                           int32_t* placement, int32_t* first_slot, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_place")) return rc;
+  SYMI_ENTER(ctx, "symi_place");
   SYMI_REQUIRE(popularity && counts && placement && first_slot, "symi_place", "NULL pointer");
   hipStream_t st = as_stream(stream);
   const int E = cfg->E, S = cfg->S_tot;
   if (E <= 64)
-    SYMI_TIMED(K_PLACE, st, (place_kernel<1><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
+    SYMI_TIMED(ctx, K_PLACE, st, (place_kernel<1><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
   else if (E <= 128)
-    SYMI_TIMED(K_PLACE, st, (place_kernel<2><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
+    SYMI_TIMED(ctx, K_PLACE, st, (place_kernel<2><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
   else if (E <= 256)
-    SYMI_TIMED(K_PLACE, st, (place_kernel<4><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
+    SYMI_TIMED(ctx, K_PLACE, st, (place_kernel<4><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
   else
-    SYMI_TIMED(K_PLACE, st, (place_kernel<16><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
+    SYMI_TIMED(ctx, K_PLACE, st, (place_kernel<16><<<1, 64, 0, st>>>(popularity, counts, placement, first_slot, E, S)));
   SYMI_LAUNCH_CHECK("symi_place");
   return SYMI_OK;
 }

@@ -23,8 +23,8 @@ __global__ void fill_i32_kernel(int32_t* p, int n, int32_t val) {
   if (i < n) p[i] = val;
 }
 
-void launch_fill_i32(int32_t* p, int n, int32_t val, hipStream_t st) {
-  if (n > 0) SYMI_TIMED(K_FILL, st, (fill_i32_kernel<<<cdiv(n, 256), 256, 0, st>>>(p, n, val)));
+void launch_fill_i32(const symi_ctx* ctx, int32_t* p, int n, int32_t val, hipStream_t st) {
+  if (n > 0) SYMI_TIMED(ctx, K_FILL, st, (fill_i32_kernel<<<cdiv(n, 256), 256, 0, st>>>(p, n, val)));
 }
 
 template <int NV>
@@ -231,35 +231,35 @@ static int route_grid(int T, int G) {
 
 using namespace symi;
 
-extern "C" int symi_route(const symi_cfg* cfg, const float* logits, int32_t* idx, float* gate,
+extern "C" int symi_route(const symi_ctx* ctx, const float* logits, int32_t* idx, float* gate,
                           int32_t* hist, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_route")) return rc;
+  SYMI_ENTER(ctx, "symi_route");
   SYMI_REQUIRE(hist && (cfg->T == 0 || (logits && idx && gate)), "symi_route", "NULL pointer");
   hipStream_t st = as_stream(stream);
   const int E = cfg->E;
-  launch_fill_i32(hist, E, 0, st);
+  launch_fill_i32(ctx, hist, E, 0, st);
   if (cfg->T > 0) {
     int G, NV;
     route_fwd_shape(E, cfg->T, G, NV);
     const int grid = route_grid(cfg->T, G);
     const size_t sh = (size_t)E * sizeof(int32_t);
     if (NV == 1)
-      SYMI_TIMED(K_ROUTE, st, (route_kernel<1><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
+      SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<1><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
     else if (NV == 2)
-      SYMI_TIMED(K_ROUTE, st, (route_kernel<2><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
+      SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<2><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
     else if (NV == 4)
-      SYMI_TIMED(K_ROUTE, st, (route_kernel<4><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
+      SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<4><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
     else
-      SYMI_TIMED(K_ROUTE, st, (route_kernel<8><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
+      SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<8><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
   }
   SYMI_LAUNCH_CHECK("symi_route");
   return SYMI_OK;
 }
 
-extern "C" int symi_route_bwd(const symi_cfg* cfg, const float* logits, const int32_t* idx,
+extern "C" int symi_route_bwd(const symi_ctx* ctx, const float* logits, const int32_t* idx,
                               const float* gate, const float* dgate, float* dlogits,
                               void* stream) {
-  if (int rc = check_cfg(cfg, "symi_route_bwd")) return rc;
+  SYMI_ENTER(ctx, "symi_route_bwd");
   if (cfg->T == 0) return SYMI_OK;
   SYMI_REQUIRE(logits && idx && gate && dgate && dlogits, "symi_route_bwd", "NULL pointer");
   hipStream_t st = as_stream(stream);
@@ -267,11 +267,11 @@ extern "C" int symi_route_bwd(const symi_cfg* cfg, const float* logits, const in
   route_shape(cfg->E, G, NV);
   const int grid = route_grid(cfg->T, G);
   if (NV == 1)
-    SYMI_TIMED(K_ROUTE_BWD, st, (route_bwd_kernel<1><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm)));
+    SYMI_TIMED(ctx, K_ROUTE_BWD, st, (route_bwd_kernel<1><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm)));
   else if (NV == 2)
-    SYMI_TIMED(K_ROUTE_BWD, st, (route_bwd_kernel<2><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm)));
+    SYMI_TIMED(ctx, K_ROUTE_BWD, st, (route_bwd_kernel<2><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm)));
   else
-    SYMI_TIMED(K_ROUTE_BWD, st, (route_bwd_kernel<4><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm)));
+    SYMI_TIMED(ctx, K_ROUTE_BWD, st, (route_bwd_kernel<4><<<grid, ROUTE_THREADS, 0, st>>>(logits, idx, gate, dgate, dlogits, cfg->T, cfg->E, cfg->k, G, cfg->renorm)));
   SYMI_LAUNCH_CHECK("symi_route_bwd");
   return SYMI_OK;
 }

@@ -345,9 +345,9 @@ __global__ __launch_bounds__(256) void router_dw_f32_kernel(const float* __restr
 
 using namespace symi;
 
-extern "C" int symi_router_fwd(const symi_cfg* cfg, const void* X, const void* Wr, const float* b,
+extern "C" int symi_router_fwd(const symi_ctx* ctx, const void* X, const void* Wr, const float* b,
                                float* logits, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_router_fwd")) return rc;
+  SYMI_ENTER(ctx, "symi_router_fwd");
   if (cfg->T == 0) return SYMI_OK;
   SYMI_REQUIRE(X && Wr && logits, "symi_router_fwd", "NULL pointer");
   hipStream_t st = as_stream(stream);
@@ -355,23 +355,23 @@ extern "C" int symi_router_fwd(const symi_cfg* cfg, const void* X, const void* W
   if (cfg->dtype == SYMI_BF16) {
     RouterParams p = {};
     p.X = X; p.Wr = Wr; p.b = b; p.logits = logits; p.T = T; p.E = E; p.d = d;
-    SYMI_TIMED(K_ROUTER_FWD, st, (router_gemm_kernel<R_FWD><<<dim3(cdiv(E, RT), cdiv(T, RT)), 256, 0, st>>>(p)));
+    SYMI_TIMED(ctx, K_ROUTER_FWD, st, (router_gemm_kernel<R_FWD><<<dim3(cdiv(E, RT), cdiv(T, RT)), 256, 0, st>>>(p)));
   } else {
-    SYMI_TIMED(K_ROUTER_FWD, st, (router_fwd_f32_kernel<<<cdiv((long long)T * E, 256), 256, 0, st>>>(
+    SYMI_TIMED(ctx, K_ROUTER_FWD, st, (router_fwd_f32_kernel<<<cdiv((long long)T * E, 256), 256, 0, st>>>(
         static_cast<const float*>(X), static_cast<const float*>(Wr), b, logits, T, E, d)));
   }
   SYMI_LAUNCH_CHECK("symi_router_fwd");
   return SYMI_OK;
 }
 
-extern "C" int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* Wr, const float* dlogits,
+extern "C" int symi_router_bwd(const symi_ctx* ctx, const void* X, const void* Wr, const float* dlogits,
                                float* dWr, float* db, void* dX, void* ws, void* stream) {
-  if (int rc = check_cfg(cfg, "symi_router_bwd")) return rc;
+  SYMI_ENTER(ctx, "symi_router_bwd");
   SYMI_REQUIRE(dWr && ws, "symi_router_bwd", "NULL pointer");
   SYMI_REQUIRE(cfg->T == 0 || (X && Wr && dlogits && dX), "symi_router_bwd", "NULL pointer");
   hipStream_t st = as_stream(stream);
   const int T = cfg->T, E = cfg->E, d = cfg->d;
-  const WsLayout L = ws_layout(cfg);
+  const WsLayout& L = ctx->L;
   if (cfg->dtype == SYMI_BF16) {
     RouterParams p = {};
     p.X = X; p.Wr = Wr; p.dl = dlogits; p.dX = dX; p.T = T; p.E = E; p.d = d;
@@ -384,24 +384,24 @@ extern "C" int symi_router_bwd(const symi_cfg* cfg, const void* X, const void* W
     p.chunk = chunk;
     const int nchunk = cdiv(T, chunk);
     if (T > 0) {
-      SYMI_TIMED(K_ROUTER_DX, st, (router_gemm_kernel<R_DX><<<dim3(cdiv(d, RT), cdiv(T, RT)), 256, 0, st>>>(p)));
-      SYMI_TIMED(K_ROUTER_DW, st, (router_gemm_kernel<R_DW><<<dim3(cdiv(d, RT), cdiv(E, RT), nchunk), 256, 0, st>>>(p)));
+      SYMI_TIMED(ctx, K_ROUTER_DX, st, (router_gemm_kernel<R_DX><<<dim3(cdiv(d, RT), cdiv(T, RT)), 256, 0, st>>>(p)));
+      SYMI_TIMED(ctx, K_ROUTER_DW, st, (router_gemm_kernel<R_DW><<<dim3(cdiv(d, RT), cdiv(E, RT), nchunk), 256, 0, st>>>(p)));
     }
     const long long n = (long long)E * d;
-    SYMI_TIMED(K_ROUTER_DW, st, (router_reduce_kernel<<<cdiv(n, 256), 256, 0, st>>>(p.partial, nchunk, n, dWr)));
+    SYMI_TIMED(ctx, K_ROUTER_DW, st, (router_reduce_kernel<<<cdiv(n, 256), 256, 0, st>>>(p.partial, nchunk, n, dWr)));
   } else {
     if (T > 0)
-      SYMI_TIMED(K_ROUTER_DX, st, (router_dx_f32_kernel<<<cdiv((long long)T * d, 256), 256, 0, st>>>(
+      SYMI_TIMED(ctx, K_ROUTER_DX, st, (router_dx_f32_kernel<<<cdiv((long long)T * d, 256), 256, 0, st>>>(
           dlogits, static_cast<const float*>(Wr), static_cast<float*>(dX), T, E, d)));
-    SYMI_TIMED(K_ROUTER_DW, st, (router_dw_f32_kernel<<<cdiv((long long)E * d, 256), 256, 0, st>>>(
+    SYMI_TIMED(ctx, K_ROUTER_DW, st, (router_dw_f32_kernel<<<cdiv((long long)E * d, 256), 256, 0, st>>>(
         dlogits, static_cast<const float*>(X), dWr, T, E, d)));
   }
   if (db) {
     float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + L.router_bias_partial);
     const int nb = cdiv(T, 256);
     if (nb > 0)
-      SYMI_TIMED(K_ROUTER_DW, st, (router_bias_partial_kernel<<<nb, 256, 0, st>>>(dlogits, T, E, part)));
-    SYMI_TIMED(K_ROUTER_DW, st, (router_bias_final_kernel<<<cdiv(E, 256), 256, 0, st>>>(part, nb, E, db)));
+      SYMI_TIMED(ctx, K_ROUTER_DW, st, (router_bias_partial_kernel<<<nb, 256, 0, st>>>(dlogits, T, E, part)));
+    SYMI_TIMED(ctx, K_ROUTER_DW, st, (router_bias_final_kernel<<<cdiv(E, 256), 256, 0, st>>>(part, nb, E, db)));
   }
   SYMI_LAUNCH_CHECK("symi_router_bwd");
   return SYMI_OK;

@@ -65,11 +65,53 @@ def test_place_host_matches_oracle():
 
 
 def test_binding_refuses_cpu_tensors_for_device_calls():
-    cfg = _cfg()
+    ctx = symi.SymiCtx(None, _cfg(), 0)     # never reaches the library: the tensors are refused first
     z = torch.zeros(64, 8)
     with pytest.raises(symi.SymiError):
-        symi.symi_route(cfg, z, torch.zeros(64, 2, dtype=torch.int32), torch.zeros(64, 2),
+        symi.symi_route(ctx, z, torch.zeros(64, 2, dtype=torch.int32), torch.zeros(64, 2),
                         torch.zeros(8, dtype=torch.int32))
+
+
+def test_context_create_and_destroy():
+    """symi_create validates on the host before it touches a device; without a usable device it
+    fails with SYMI_EHIP and a message; device calls refuse a NULL context; destroying NULL is
+    allowed.  With a GPU: contexts are created and destroyed repeatedly, with every flag."""
+    import ctypes
+    L = symi.lib()
+    out = ctypes.c_void_p()
+    assert L.symi_create(None, 0, ctypes.byref(out)) == -1 and not out.value
+    assert L.symi_create(ctypes.byref(_cfg()), 0, None) == -1
+    assert L.symi_create(ctypes.byref(_cfg(S_tot=7)), 0, ctypes.byref(out)) == -1 and not out.value
+    assert L.symi_create(ctypes.byref(_cfg()), 8, ctypes.byref(out)) == -1      # unknown flag bit
+    assert "flag" in symi.symi_last_error()
+    assert L.symi_destroy(None) == 0
+    assert L.symi_route(None, None, None, None, None, None) == -1
+    assert "ctx" in symi.symi_last_error()
+    assert L.symi_timing_reset(None) == -1
+    if not torch.cuda.is_available():
+        with pytest.raises(symi.SymiError, match="device"):
+            symi.symi_create(_cfg())
+        assert L.symi_create(ctypes.byref(_cfg()), 0, ctypes.byref(out)) == -3 and not out.value
+        return
+    for flags in (0, symi.CTX_NO_OVERLAP, symi.CTX_NO_SLICING, symi.CTX_TIMING,
+                  symi.CTX_NO_OVERLAP | symi.CTX_NO_SLICING | symi.CTX_TIMING) * 3:
+        ctx = symi.symi_create(_cfg(dtype="bf16"), flags)
+        assert ctx.ptr and ctx.T == 64 and ctx.flags == flags
+        symi.symi_destroy(ctx)
+        assert ctx.ptr is None
+        symi.symi_destroy(ctx)               # a second destroy of the handle is a no-op
+
+
+def test_launch_limits_are_rejected_as_unsupported():
+    """Shapes whose grids or 32-bit offsets the kernels cannot address are refused up front."""
+    ok = dict(T=1 << 20, E=8, k=8, d=64, f=64, S_tot=16, N=1, dtype="bf16")
+    assert symi.symi_validate(_cfg(**ok)) == 0
+    for bad in (dict(ok, T=1 << 22, k=4),                 # 65536 + 16 + 256 m-tiles
+                dict(ok, dtype="f32"),                    # fp32 tiles are a quarter the rows
+                dict(ok, T=(1 << 23) + 1024, k=1, E=1, S_tot=1),   # T / 128 > 65535
+                dict(ok, T=64, d=1 << 16, f=1 << 14)):    # 2*f*d = 2^31
+        assert symi.symi_validate(_cfg(**bad)) == -2, bad
+        assert symi.symi_workspace_bytes(_cfg(**bad)) == 0
 
 
 def test_slot_capacity_host_function_matches_oracle():

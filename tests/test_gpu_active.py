@@ -6,8 +6,8 @@ import torch
 
 import paper_2504_19925_amd as symi
 import workloads as wl
-from tests import harness as Hn
-from tests.test_gpu_parity import _small, check_iteration
+import harness as Hn
+from tests.checks import check_iteration, small as _small
 
 pytestmark = pytest.mark.gpu
 
@@ -72,7 +72,7 @@ def test_active_adam_requires_the_current_placement():
     lib = symi.binding.lib()
     import ctypes
     rc = lib.symi_adam_to_replicas_active(
-        ctypes.byref(st.cfg), ctypes.byref(adam), st.dW1.data_ptr(), st.dW2.data_ptr(),
+        st.ctx.ptr, ctypes.byref(adam), st.dW1.data_ptr(), st.dW2.data_ptr(),
         st.master.data_ptr(), st.m.data_ptr(), st.v.data_ptr(), None, None,
         st.first_slot_next.data_ptr(), st.W1s.data_ptr(), st.W2s.data_ptr(), None)
     assert rc == -1 and "NULL" in symi.symi_last_error()

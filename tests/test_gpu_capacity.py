@@ -11,9 +11,9 @@ import torch
 import paper_2504_19925_amd as symi
 import workloads as wl
 from oracle import symi_oracle as O
-from tests import harness as Hn
-from tests.test_gpu_parity import _small
-from tests.util import check_close
+import harness as Hn
+from tests.checks import small as _small
+from harness.metrics import check_close
 
 pytestmark = pytest.mark.gpu
 
@@ -26,7 +26,7 @@ def _run(c, capacity_factor, it=0, uniform=False):
         # placement from the previous iteration's popularity (the paper's policy)
         st.hist_prev.copy_(torch.from_numpy(O.route(Hn.npf(Hn.draw_inputs(c, it - 1)[1]), c.k, True)[2]).int())
     st.place_current()
-    cap = symi.symi_slot_capacity(st.cfg, capacity_factor)
+    cap = symi.symi_slot_capacity(st.ctx, capacity_factor)
     assert cap == O.slot_capacity(capacity_factor, c.A, c.S_tot)
     st.forward(X, logits, slot_cap=cap)
     st.backward(dY, logits)
@@ -87,26 +87,26 @@ def test_survival_adaptive_vs_uniform_placement_full_size(name, iters):
     """The paper's central quantity at full size (integers only): survival under the
     placement that mimics the previous iteration against the static uniform placement."""
     c = wl.get_config(name)
-    cfg = Hn.make_cfg(c)
+    ctx = Hn.make_ctx(c)
     dev = "cuda"
     i32 = dict(dtype=torch.int32, device=dev)
-    ws = torch.empty(symi.symi_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
-    X = torch.zeros(c.T, c.d, dtype=cfg.torch_dtype, device=dev)
-    Xp = torch.empty(c.A, c.d, dtype=cfg.torch_dtype, device=dev)
+    ws = torch.empty(symi.symi_workspace_bytes(ctx), dtype=torch.uint8, device=dev)
+    X = torch.zeros(c.T, c.d, dtype=ctx.torch_dtype, device=dev)
+    Xp = torch.empty(c.A, c.d, dtype=ctx.torch_dtype, device=dev)
     idx = torch.empty(c.T, c.k, **i32); gate = torch.empty(c.T, c.k, dtype=torch.float32, device=dev)
     hist = torch.empty(c.E, **i32)
     counts = torch.empty(c.E, **i32); placement = torch.empty(c.S_tot, **i32); first = torch.empty(c.E + 1, **i32)
     roa = torch.empty(c.A, **i32); aor = torch.empty(c.A, **i32); off = torch.empty(c.S_tot + 1, **i32)
-    cap = symi.symi_slot_capacity(cfg, 1.0)
+    cap = symi.symi_slot_capacity(ctx, 1.0)
     prev = torch.zeros(c.E, **i32)
     for it in range(iters):
         logits = wl.make_logits(c, it).to(dev)
-        symi.symi_route(cfg, logits, idx, gate, hist)
+        symi.symi_route(ctx, logits, idx, gate, hist)
         o_idx, _, o_hist = O.route(logits.cpu().numpy(), c.k, True)
         surv = {}
         for mode, pop in (("adaptive", prev), ("uniform", torch.zeros(c.E, **i32))):
-            symi.symi_place(cfg, pop, counts, placement, first)
-            symi.symi_dispatch_capacity(cfg, cap, X, idx, hist, counts, first, roa, aor, off, Xp, ws)
+            symi.symi_place(ctx, pop, counts, placement, first)
+            symi.symi_dispatch_capacity(ctx, cap, X, idx, hist, counts, first, roa, aor, off, Xp, ws)
             Hn.sync()
             oc, _, of = O.place(pop.cpu().numpy(), c.S_tot)
             o_roa, o_aor, o_off, keep = O.dispatch_capacity(o_idx, oc, of, cap)

@@ -8,8 +8,8 @@ import torch
 import paper_2504_19925_amd as symi
 import workloads as wl
 from oracle import symi_oracle as O
-from tests import harness as Hn
-from tests.util import check_close, relerr_elem, TOL
+import harness as Hn
+from harness.metrics import check_close, relerr_elem, TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -32,11 +32,11 @@ def test_router_capacity_and_replica_path_on_edge_shapes(dtype):
     for c in _cases(dtype):
         print(f"[edge] {c}", flush=True)
         st = Hn.State(c)
-        s, cfg = st, st.cfg
+        s, ctx = st, st.ctx
         X, _, dY = Hn.draw_inputs(c, 0)
         Wr, b = wl.make_router(c, 0, "cuda")
         logits = torch.zeros(c.T, c.E, dtype=torch.float32, device="cuda")
-        symi.symi_router_fwd(cfg, X, Wr, b, logits)
+        symi.symi_router_fwd(ctx, X, Wr, b, logits)
         Hn.sync()
         Xn, Wn, bn, dYn = Hn.npf(X), Hn.npf(Wr), Hn.npf(b), Hn.npf(dY)
         if c.T:
@@ -45,16 +45,16 @@ def test_router_capacity_and_replica_path_on_edge_shapes(dtype):
         # ---- capacity of ONE row per slot, then the per-slot gradient path on the kept rows
         st.place_current()
         st.forward(X, logits, slot_cap=1)
-        symi.symi_combine_bwd(cfg, dY, s.Yp, s.row_of_assign, s.gate, s.dYp, s.dgate)
+        symi.symi_combine_bwd(ctx, dY, s.Yp, s.row_of_assign, s.gate, s.dYp, s.dgate)
         g1 = torch.full((c.S_tot, 2 * c.f, c.d), float("nan"), dtype=torch.float32, device="cuda")
         g2 = torch.full((c.S_tot, c.d, c.f), float("nan"), dtype=torch.float32, device="cuda")
-        symi.symi_expert_bwd_slots(cfg, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
+        symi.symi_expert_bwd_slots(ctx, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
                                    s.dXp, g1, g2, s.ws)
-        symi.symi_dispatch_bwd(cfg, s.dXp, s.row_of_assign, s.dX)
-        symi.symi_route_bwd(cfg, logits, s.idx, s.gate, s.dgate, s.dlogits)
+        symi.symi_dispatch_bwd(ctx, s.dXp, s.row_of_assign, s.dX)
+        symi.symi_route_bwd(ctx, logits, s.idx, s.gate, s.dgate, s.dlogits)
         dWr = torch.empty(c.E, c.d, dtype=torch.float32, device="cuda")
         db = torch.empty(c.E, dtype=torch.float32, device="cuda")
-        symi.symi_router_bwd(cfg, X, Wr, s.dlogits, dWr, db, s.dX, s.ws)
+        symi.symi_router_bwd(ctx, X, Wr, s.dlogits, dWr, db, s.dX, s.ws)
         Hn.sync()
         o_idx, o_gate, _ = O.route(zn, c.k, True)
         o_counts, o_place, o_first = O.place(np.zeros(c.E, dtype=np.int64), c.S_tot)
@@ -83,6 +83,6 @@ def test_router_capacity_and_replica_path_on_edge_shapes(dtype):
             assert not dWr.any() and not db.any()
         # ---- the all-reduce over the replicas, average over the class's replicas
         r1 = O.replica_allreduce(Hn.npf(g1), o_first, 0.5)
-        symi.symi_replica_allreduce(cfg, s.first_slot, 0.5, g1, g2)
+        symi.symi_replica_allreduce(ctx, s.first_slot, 0.5, g1, g2)
         Hn.sync()
         assert relerr_elem(Hn.npf(g1), r1) <= TOL["f32"]

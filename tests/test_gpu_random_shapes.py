@@ -9,8 +9,8 @@ import pytest
 import torch
 
 import workloads as wl
-from tests import harness as Hn
-from tests.test_gpu_parity import check_iteration
+import harness as Hn
+from tests.checks import check_iteration
 import tests.test_gpu_next_edges as next_edges
 
 pytestmark = pytest.mark.gpu

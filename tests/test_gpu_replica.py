@@ -7,9 +7,9 @@ import torch
 
 import paper_2504_19925_amd as symi
 from oracle import symi_oracle as O
-from tests import harness as Hn
-from tests.test_gpu_parity import _small
-from tests.util import check_close, relerr_elem, TOL
+import harness as Hn
+from tests.checks import small as _small
+from harness.metrics import check_close, relerr_elem, TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -24,11 +24,11 @@ def test_replica_gradient_path(name, it, scale):
     st.place_current()
     st.forward(X, logits)
     st.backward(dY, logits)                         # fused per-class gradients in st.dW1 / st.dW2
-    s, cfg = st, st.cfg
+    s, ctx = st, st.ctx
     g1 = torch.full((c.S_tot, 2 * c.f, c.d), float("nan"), dtype=torch.float32, device="cuda")
     g2 = torch.full((c.S_tot, c.d, c.f), float("nan"), dtype=torch.float32, device="cuda")
     dXp2 = torch.empty_like(s.dXp)
-    symi.symi_expert_bwd_slots(cfg, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
+    symi.symi_expert_bwd_slots(ctx, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
                                dXp2, g1, g2, s.ws)
     Hn.sync()
     assert torch.equal(dXp2, s.dXp)                 # the data gradient does not depend on the variant
@@ -47,7 +47,7 @@ def test_replica_gradient_path(name, it, scale):
     # ---- the all-reduce on its own (fed the GPU's per-slot gradients): an fp32 computation
     r1 = O.replica_allreduce(Hn.npf(g1), o_first, scale)
     r2 = O.replica_allreduce(Hn.npf(g2), o_first, scale)
-    symi.symi_replica_allreduce(cfg, s.first_slot, scale, g1, g2)
+    symi.symi_replica_allreduce(ctx, s.first_slot, scale, g1, g2)
     Hn.sync()
     assert relerr_elem(Hn.npf(g1), r1) <= TOL["f32"] and relerr_elem(Hn.npf(g2), r2) <= TOL["f32"]
     # every replica of a class holds the same bits as its representative
@@ -78,17 +78,17 @@ def test_replica_path_full_size_c2_matches_fused_path():
     st.place_current()                                  # replicas proportional to iteration 0's popularity
     st.forward(X0, logits0)
     st.backward(dY0, logits0)
-    s, cfg = st, st.cfg
+    s, ctx = st, st.ctx
     g1 = torch.full((c.S_tot, 2 * c.f, c.d), float("nan"), dtype=torch.float32, device="cuda")
     g2 = torch.full((c.S_tot, c.d, c.f), float("nan"), dtype=torch.float32, device="cuda")
-    symi.symi_expert_bwd_slots(cfg, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
+    symi.symi_expert_bwd_slots(ctx, s.dYp, s.Xp, s.UV, s.H, s.slot_offsets, s.first_slot, s.W1s, s.W2s,
                                s.dXp, g1, g2, s.ws)
     Hn.sync()
     off = s.slot_offsets.cpu().numpy()
     assert int(s.counts.max()) > 4                      # the hot classes really are replicated
     for q in np.nonzero(np.diff(off) == 0)[0][:8]:
         assert not g1[q].any() and not g2[q].any()
-    symi.symi_replica_allreduce(cfg, s.first_slot, 1.0, g1, g2)
+    symi.symi_replica_allreduce(ctx, s.first_slot, 1.0, g1, g2)
     Hn.sync()
     pl = s.placement.long()
     for e in torch.unique(pl).tolist()[:6] + [int(s.counts.argmax())]:

@@ -8,9 +8,9 @@ import torch
 import paper_2504_19925_amd as symi
 import workloads as wl
 from oracle import symi_oracle as O
-from tests import harness as Hn
-from tests.test_gpu_parity import _small
-from tests.util import check_close, relerr_elem, TOL
+import harness as Hn
+from tests.checks import small as _small
+from harness.metrics import check_close, relerr_elem, TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -22,14 +22,14 @@ def test_router_closes_the_layer(name):
     X, _, dY = Hn.draw_inputs(c, 0)
     Wr, b = wl.make_router(c, 0, "cuda")
     logits = torch.empty(c.T, c.E, dtype=torch.float32, device="cuda")
-    symi.symi_router_fwd(st.cfg, X, Wr, b, logits)
+    symi.symi_router_fwd(st.ctx, X, Wr, b, logits)
     Hn.sync()
     Xn, Wn, bn, dYn = Hn.npf(X), Hn.npf(Wr), Hn.npf(b), Hn.npf(dY)
     log = {}
     check_close("logits", Hn.npf(logits), O.router_forward(Xn, Wn, bn), c.dtype, log=log)
     # without bias
     l2 = torch.empty_like(logits)
-    symi.symi_router_fwd(st.cfg, X, Wr, None, l2)
+    symi.symi_router_fwd(st.ctx, X, Wr, None, l2)
     check_close("logits_nobias", Hn.npf(l2), O.router_forward(Xn, Wn), c.dtype, log=log)
     # ---- the layer on the GPU's logits, then the router's backward
     st.place_current()
@@ -38,7 +38,7 @@ def test_router_closes_the_layer(name):
     dX_experts = st.dX.clone()
     dWr = torch.empty(c.E, c.d, dtype=torch.float32, device="cuda")
     db = torch.empty(c.E, dtype=torch.float32, device="cuda")
-    symi.symi_router_bwd(st.cfg, X, Wr, st.dlogits, dWr, db, st.dX, st.ws)
+    symi.symi_router_bwd(st.ctx, X, Wr, st.dlogits, dWr, db, st.dX, st.ws)
     Hn.sync()
     zn = Hn.npf(logits)
     o_idx, o_gate, _ = O.route(zn, c.k, True)
@@ -64,7 +64,7 @@ def test_router_closes_the_layer(name):
     # bf16 dX it would drown in that sum's rounding)
     dXr = torch.zeros_like(st.dX)
     dWr2, db2 = torch.empty_like(dWr), torch.empty_like(db)
-    symi.symi_router_bwd(st.cfg, X, Wr, st.dlogits, dWr2, db2, dXr, st.ws)
+    symi.symi_router_bwd(st.ctx, X, Wr, st.dlogits, dWr2, db2, dXr, st.ws)
     Hn.sync()
     check_close("dXr_iso", Hn.npf(dXr), i_dXr, c.dtype, log=log)
     assert torch.equal(dWr2, dWr) and torch.equal(db2, db)          # deterministic
@@ -77,18 +77,18 @@ def test_router_full_size_sampled_c5():
     """Config c5's full shape (T=65536, d=4096, E=128): sampled logits rows, sampled dWr
     columns and sampled dX rows against the oracle."""
     c = wl.get_config("c5")
-    cfg = Hn.make_cfg(c)
+    ctx = Hn.make_ctx(c)
     X = wl.make_tokens(c, 0, "cuda")
     Wr, b = wl.make_router(c, 0, "cuda")
     g = torch.Generator(device="cuda"); g.manual_seed(9)
     dl = torch.randn(c.T, c.E, generator=g, device="cuda", dtype=torch.float32)
     logits = torch.empty(c.T, c.E, dtype=torch.float32, device="cuda")
-    dX = torch.zeros(c.T, c.d, dtype=cfg.torch_dtype, device="cuda")
+    dX = torch.zeros(c.T, c.d, dtype=ctx.torch_dtype, device="cuda")
     dWr = torch.empty(c.E, c.d, dtype=torch.float32, device="cuda")
     db = torch.empty(c.E, dtype=torch.float32, device="cuda")
-    ws = torch.empty(symi.symi_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
-    symi.symi_router_fwd(cfg, X, Wr, b, logits)
-    symi.symi_router_bwd(cfg, X, Wr, dl, dWr, db, dX, ws)
+    ws = torch.empty(symi.symi_workspace_bytes(ctx), dtype=torch.uint8, device="cuda")
+    symi.symi_router_fwd(ctx, X, Wr, b, logits)
+    symi.symi_router_bwd(ctx, X, Wr, dl, dWr, db, dX, ws)
     Hn.sync()
     rows = torch.randint(0, c.T, (64,), generator=torch.Generator().manual_seed(1)).tolist() + [0, c.T - 1]
     Xs, Wn, bn = Hn.npf(X[rows]), Hn.npf(Wr), Hn.npf(b)

@@ -69,16 +69,18 @@ def _random_placement(rng, E, S):
     return O.place(rng.multinomial(3000, rng.dirichlet(np.full(E, 0.3))), S)[1]
 
 
-def test_get_source_properties():
+def test_source_matrix_properties():
     rng = np.random.default_rng(1)
     for _ in range(30):
         N = int(rng.choice([2, 4, 8, 16])); s = int(rng.integers(1, 5)); S = N * s
         E = int(rng.integers(1, S + 1))
         pl = _random_placement(rng, E, S)
+        hosted = O.host_table(pl, N, E)
+        src = O.source_matrix(pl, N, E)
         for e in range(E):
-            hosts = O.hosts_of(pl, N, e)
-            assert hosts == sorted({q // s for q in range(S) if pl[q] == e}) and hosts
-            srcs = [O.get_source(pl, N, e, r) for r in range(N)]
+            hosts = sorted({q // s for q in range(S) if pl[q] == e})   # brute force over the slots
+            assert np.flatnonzero(hosted[e]).tolist() == hosts and hosts
+            srcs = src[e].tolist()
             assert all(x in hosts for x in srcs)                       # the source owns a replica
             assert all(srcs[r] == r for r in hosts)                    # local communication first
             remote = [srcs[r] for r in range(N) if r not in hosts]
@@ -89,25 +91,28 @@ def test_get_source_properties():
         # every (class, destination) pair is sent exactly once, by the rank the receiver expects
         sent = {}
         for rank in range(N):
-            recv, send = O.collect_grads(pl, N, E, rank)
-            assert set(recv) == set(range(E)) and all(v[1] == rank for v in recv.values())
-            for e, lst in send.items():
-                for dst, part in lst:
-                    assert dst == part and (e, dst) not in sent
+            recv_src, send = O.gradient_plan(pl, N, E, rank)
+            assert recv_src.shape == (E,)
+            assert set(send) == {e for e in range(E) if hosted[e, rank]}
+            for e, dsts in send.items():
+                assert dsts == sorted(dsts)
+                for dst in dsts:
+                    assert (e, dst) not in sent
                     sent[(e, dst)] = rank
         assert len(sent) == E * N
         for rank in range(N):
-            recv, _ = O.collect_grads(pl, N, E, rank)
-            assert all(sent[(e, rank)] == recv[e][0] for e in range(E))
+            recv_src, _ = O.gradient_plan(pl, N, E, rank)
+            assert all(sent[(e, rank)] == recv_src[e] for e in range(E))
 
 
 def test_paper_example_of_intra_rank_replication_is_plannable():
     # Sec. 4.1's example: 8 ranks, 2 slots each, 4 classes with 5, 5, 4, 2 instances
     pl = np.repeat(np.arange(4), [5, 5, 4, 2])
-    assert O.hosts_of(pl, 8, 0) == [0, 1, 2] and O.hosts_of(pl, 8, 1) == [2, 3, 4]
-    assert O.hosts_of(pl, 8, 2) == [5, 6] and O.hosts_of(pl, 8, 3) == [7]
-    assert [O.get_source(pl, 8, 3, r) for r in range(8)] == [7] * 8
-    assert [O.get_source(pl, 8, 2, r) for r in range(8)] == [5, 6, 5, 6, 5, 5, 6, 6]
+    hosted = O.host_table(pl, 8, 4)
+    assert [np.flatnonzero(h).tolist() for h in hosted] == [[0, 1, 2], [2, 3, 4], [5, 6], [7]]
+    src = O.source_matrix(pl, 8, 4)
+    assert src[3].tolist() == [7] * 8
+    assert src[2].tolist() == [5, 6, 5, 6, 5, 5, 6, 6]
 
 
 def test_rank_group_enumeration():
@@ -136,14 +141,13 @@ def test_library_twins_match_the_oracle():
             off = torch.empty(E + 1, dtype=torch.int32)
             dst = torch.empty(E * N, dtype=torch.int32)
             n = symi.symi_collect_grads(cfg, plt, rank, recv_src, off, dst)
-            recv, send = O.collect_grads(pl, N, E, rank)
-            assert recv_src.tolist() == [recv[e][0] for e in range(E)]
+            want_src, send = O.gradient_plan(pl, N, E, rank)
+            assert recv_src.tolist() == want_src.tolist()
             assert off[E] == n == sum(len(v) for v in send.values())
             for e in range(E):
-                got = dst[off[e]:off[e + 1]].tolist()
-                assert got == [d for d, _ in send.get(e, [])]
+                assert dst[off[e]:off[e + 1]].tolist() == send.get(e, [])
             e = rnd.randrange(E)
-            assert symi.symi_grad_source(cfg, plt, e, rank) == O.get_source(pl, N, e, rank)
+            assert symi.symi_grad_source(cfg, plt, e, rank) == want_src[e]
         with pytest.raises(symi.SymiError):
             symi.symi_grad_source(cfg, plt, E, 0)
     got = symi.symi_comm_cost(**EXAMPLE)
