@@ -371,7 +371,7 @@ def summary(out):
 def cpu_baseline(c):
     """The oracle as it stands, timed on a bounded sample of the same workload: whole
     iterations on the first Ts tokens (all classes, full widths), Ts chosen so that one
-    sampled iteration is about 1.5 TFLOP of fp64 work."""
+    sampled iteration is at most 0.75 TFLOP of fp64 work."""
     import numpy as np
     import torch
     import workloads as wl
@@ -384,7 +384,7 @@ def cpu_baseline(c):
 
     per_token = 18.0 * c.k * c.d * c.f
     Ts = c.T
-    while Ts > 256 and Ts * per_token > 1.5e12:
+    while Ts > 256 and Ts * per_token > 0.75e12:
         Ts //= 2
     Es = min(c.E, 64)                        # classes whose shard the sampled Adam step covers
     dev = "cuda" if torch.cuda.is_available() else "cpu"     # where the inputs are drawn, nothing else
