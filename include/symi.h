@@ -148,6 +148,23 @@ int symi_dispatch(const symi_ctx* ctx, const void* X, const int32_t* idx, const 
                   int32_t* assign_of_row, int32_t* slot_offsets, void* Xp, void* ws,
                   void* stream);
 
+/* symi_dispatch for callers that cannot allocate or bring a workspace along: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs
+ * and results as symi_dispatch, bit for bit; the scratch (per-chunk class counts) lives in a
+ * buffer of SYMI_DISPATCH_NOALLOC_SCRATCH_BYTES that is part of the library's code object (one
+ * copy per GPU, held until the process ends; its address on the context's device is looked up
+ * by symi_create).  The call allocates nothing and creates nothing.
+ *   Limit: (ceil(T*k/1024) + 1) * E * 4 + 12 * E bytes (each term rounded up to 256) must fit
+ *   the buffer, else SYMI_EUNSUPPORTED; a context created with SYMI_CTX_TIMING is refused
+ *   (SYMI_EINVAL: such a context creates events per launch).
+ *   All calls on one GPU share the one buffer, whatever their context or stream: calls that may
+ *   overlap in time on a GPU race.  Nothing in it has to start at zero (every entry read was
+ *   written earlier in the same call), so its contents after a call do not matter to the next. */
+#define SYMI_DISPATCH_NOALLOC_SCRATCH_BYTES (4u << 20)
+int symi_dispatch_noalloc(const symi_ctx* ctx, const void* X, const int32_t* idx, const int32_t* hist,
+                          const int32_t* counts, const int32_t* first_slot, int32_t* row_of_assign,
+                          int32_t* assign_of_row, int32_t* slot_offsets, void* Xp, void* stream);
+
 /* Expert capacity under adaptive replication (Sec. 3.4):
  *   slot_capacity = capacity_factor * tokens_per_batch / (s*N),  capacity(e_i) = slot_capacity * r_i.
  * HOST function: returns slot_capacity for cfg (tokens_per_batch = T*k assignments), the

@@ -16,7 +16,7 @@ _LIB = None
 EXPORTS = [
     "symi_validate", "symi_create", "symi_destroy", "symi_workspace_bytes", "symi_last_error",
     "symi_route", "symi_route_bwd", "symi_place", "symi_place_host", "symi_dispatch",
-    "symi_slot_capacity", "symi_dispatch_capacity", "symi_dispatch_bwd", "symi_expert_fwd",
+    "symi_dispatch_noalloc", "symi_slot_capacity", "symi_dispatch_capacity", "symi_dispatch_bwd", "symi_expert_fwd",
     "symi_expert_bwd", "symi_combine", "symi_combine_bwd", "symi_adam_to_replicas",
     "symi_expert_bwd_slots", "symi_expert_bwd_active", "symi_adam_to_replicas_active",
     "symi_replica_allreduce", "symi_router_fwd", "symi_router_bwd",
@@ -113,6 +113,7 @@ def lib():
             "symi_place": ([ctx, ip, ip, ip, ip, vp], ci),
             "symi_place_host": ([cfgp, ip, ip, ip, ip], ci),
             "symi_dispatch": ([ctx, vp, ip, ip, ip, ip, ip, ip, ip, vp, vp, vp], ci),
+            "symi_dispatch_noalloc": ([ctx, vp, ip, ip, ip, ip, ip, ip, ip, vp, vp], ci),
             "symi_slot_capacity": ([cfgp, cd], ci),
             "symi_dispatch_capacity": ([ctx, ci, vp, ip, ip, ip, ip, ip, ip, ip, vp, vp, vp], ci),
             "symi_dispatch_bwd": ([ctx, vp, ip, vp, vp], ci),
@@ -266,6 +267,19 @@ def symi_dispatch(ctx, X, idx, hist, counts, first_slot, row_of_assign, assign_o
         _dev(assign_of_row, I32, "assign_of_row", ctx.A),
         _dev(slot_offsets, I32, "slot_offsets", ctx.S_tot + 1), _dev(Xp, dt, "Xp", ctx.A * ctx.d),
         _dev(ws, torch.uint8, "ws", symi_workspace_bytes(ctx.cfg)), _stream()), "symi_dispatch")
+
+
+def symi_dispatch_noalloc(ctx, X, idx, hist, counts, first_slot, row_of_assign, assign_of_row,
+                          slot_offsets, Xp):
+    dt = ctx.torch_dtype
+    _check(lib().symi_dispatch_noalloc(
+        ctx.ptr, _dev(X, dt, "X", ctx.T * ctx.d), _dev(idx, I32, "idx", ctx.A),
+        _dev(hist, I32, "hist", ctx.E), _dev(counts, I32, "counts", ctx.E),
+        _dev(first_slot, I32, "first_slot", ctx.E + 1),
+        _dev(row_of_assign, I32, "row_of_assign", ctx.A),
+        _dev(assign_of_row, I32, "assign_of_row", ctx.A),
+        _dev(slot_offsets, I32, "slot_offsets", ctx.S_tot + 1), _dev(Xp, dt, "Xp", ctx.A * ctx.d),
+        _stream()), "symi_dispatch_noalloc")
 
 
 def symi_slot_capacity(cfg, capacity_factor):

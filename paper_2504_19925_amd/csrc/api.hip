@@ -188,6 +188,11 @@ int symi_create(const symi_cfg* cfg, unsigned flags, symi_ctx** out) {
   ctx->side = nullptr;
   ctx->fork = ctx->mid = ctx->join = nullptr;
   for (auto& e : ctx->open) e = nullptr;
+  ctx->static_scratch = nullptr;
+  if (int rc = symi::static_scratch_address(dev, &ctx->static_scratch)) {
+    delete ctx;
+    return rc;
+  }
   if (ctx->overlap && symi::wants_side_stream(cfg, cus)) {
     // default priority, non-blocking with respect to the NULL stream
     const bool ok = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess &&

@@ -102,6 +102,8 @@ struct symi_ctx {
   // (nullptr when the flags or the shape rule it out)
   hipStream_t side;
   hipEvent_t fork, mid, join;
+  // device address of the static scratch of symi_dispatch_noalloc on `device`
+  void* static_scratch;
   mutable std::vector<symi::TimedLaunch> launches;
   mutable hipEvent_t open[symi::K_COUNT];
 };
@@ -111,6 +113,7 @@ constexpr uint32_t CTX_MAGIC = 0x53594d49u;   // "SYMI"
 int enter(const symi_ctx* ctx, const char* who);
 void timing_begin(const symi_ctx* ctx, int kid, hipStream_t st);
 void timing_end(const symi_ctx* ctx, int kid, hipStream_t st);
+int static_scratch_address(int device, void** out);   // dispatch.hip
 void launch_fill_i32(const symi_ctx* ctx, int32_t* p, int n, int32_t val, hipStream_t st);
 }  // namespace symi
 

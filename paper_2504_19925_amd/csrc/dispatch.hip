@@ -20,7 +20,15 @@
 // kept ones are packed without gaps and spread over the replicas as before.
 #include <math.h>
 
+#include <mutex>
+
 #include "common.h"
+
+// Scratch of symi_dispatch_noalloc (the per-chunk class counts and the per-class capacity
+// table that symi_dispatch keeps in the caller's workspace).  Every GPU the library runs on
+// holds its own copy at its own address until the process ends; host code never uses this name
+// as an address, only the pointer hipGetSymbolAddress returned for the device in question.
+static __device__ __align__(256) unsigned char scratch[SYMI_DISPATCH_NOALLOC_SCRATCH_BYTES];
 
 namespace symi {
 
@@ -283,6 +291,33 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const void* __restrict
   }
 }
 
+// Device address of `scratch` on `device`, which must be the current device: looked up once per
+// device and kept (each GPU holds its own copy of the array at its own address).
+int static_scratch_address(int device, void** out) {
+  constexpr int MAX_DEV = 64;
+  static std::mutex mu;
+  static void* addr[MAX_DEV] = {};
+  *out = nullptr;
+  if (device < 0 || device >= MAX_DEV) {
+    set_error("symi_create: device ordinal %d outside [0, %d)", device, MAX_DEV);
+    return SYMI_EUNSUPPORTED;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      (void)hipGetLastError();
+      set_error("symi_create: hipGetSymbolAddress of the static scratch failed on device %d: %s", device,
+                hipGetErrorString(e));
+      return SYMI_EHIP;
+    }
+    addr[device] = p;
+  }
+  *out = addr[device];
+  return SYMI_OK;
+}
+
 static int grid_for(long long work_items, int per_block) {
   long long g = (work_items + per_block - 1) / per_block;
   if (g < 1) g = 1;
@@ -330,6 +365,28 @@ extern "C" int symi_dispatch(const symi_ctx* ctx, const void* X, const int32_t* 
                              void* Xp, void* ws, void* stream) {
   return dispatch_impl("symi_dispatch", ctx, 0, X, idx, hist, counts, first_slot, row_of_assign,
                        assign_of_row, slot_offsets, Xp, ws, stream);
+}
+
+extern "C" int symi_dispatch_noalloc(const symi_ctx* ctx, const void* X, const int32_t* idx,
+                                     const int32_t* hist, const int32_t* counts,
+                                     const int32_t* first_slot, int32_t* row_of_assign,
+                                     int32_t* assign_of_row, int32_t* slot_offsets, void* Xp,
+                                     void* stream) {
+  const char* who = "symi_dispatch_noalloc";
+  if (int rc = enter(ctx, who)) return rc;
+  // a timing context creates two events per launch, which allocates
+  SYMI_REQUIRE(!ctx->timing, who, "the context was created with SYMI_CTX_TIMING");
+  // the same layout as the head of the caller's workspace: counts of every chunk, class table
+  const size_t need = ctx->L.tile_map;
+  if (need > (size_t)SYMI_DISPATCH_NOALLOC_SCRATCH_BYTES) {
+    set_error("%s: T*k = %lld assignments in %d classes need %zu bytes of scratch, the static buffer holds %zu "
+              "((ceil(T*k/1024)+1)*E*4 + 12*E, each rounded up to 256): use symi_dispatch with a workspace",
+              who, (long long)ctx->cfg.T * ctx->cfg.k, ctx->cfg.E, need, (size_t)SYMI_DISPATCH_NOALLOC_SCRATCH_BYTES);
+    return SYMI_EUNSUPPORTED;
+  }
+  SYMI_REQUIRE(ctx->static_scratch != nullptr, who, "the context holds no address of the static scratch");
+  return dispatch_impl(who, ctx, 0, X, idx, hist, counts, first_slot, row_of_assign, assign_of_row,
+                       slot_offsets, Xp, ctx->static_scratch, stream);
 }
 
 extern "C" int symi_slot_capacity(const symi_cfg* cfg, double capacity_factor) {
