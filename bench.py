@@ -169,6 +169,90 @@ def extras(args):
     print(json.dumps(out))
 
 
+def ceilings(args):
+    """What this GPU sustains with the instruction and access mixes of the hot path's kernels
+    (in-bounds microbenchmarks of libsymi_ceilings.so and of torch's fill / copy); one JSON line.
+    Every figure is the average of `reps` back-to-back launches between two events on the
+    launch stream."""
+    import ctypes
+    import torch
+
+    path = os.path.join(ROOT, "paper_2504_19925_amd", "libsymi_ceilings.so")
+    if not os.path.exists(path):
+        raise SystemExit(f"{path} not found: build it with `python -m paper_2504_19925_amd.build`")
+    L = ctypes.CDLL(path)
+    vp, ci, cll = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong
+    L.symi_ceiling_mfma.argtypes = [vp, vp, ci, ci, vp]
+    L.symi_ceiling_gemm_loop.argtypes = [ci, vp, vp, vp, ci, ci, ci, cll, cll, vp]
+    L.symi_ceiling_adam_streams.argtypes = [ci, vp, vp, vp, vp, vp, vp, cll, ci, vp]
+    torch.cuda.set_device(0)
+    stream = lambda: ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ptr = lambda t: ctypes.c_void_p(t.data_ptr())
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    def call(rc):
+        if rc != 0:
+            raise SystemExit(f"ceiling launch failed ({rc})")
+
+    out = {"unit_note": "TFLOP/s for mfma and gemm_loop, GB/s for the streams", "reps": args.steps}
+    g = torch.Generator(device="cuda").manual_seed(1)
+    # ---- MFMA from registers: 1024 workgroups (4 per CU), 4000 x 16 MFMAs per wavefront
+    blocks, iters = 1024, 4000
+    res = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    for name, ops in (("random", torch.randn(blocks * 256 * 16, generator=g, device="cuda").to(torch.bfloat16)),
+                      ("zeros", torch.zeros(blocks * 256 * 16, dtype=torch.bfloat16, device="cuda"))):
+        s = timed(lambda: call(L.symi_ceiling_mfma(ptr(ops), ptr(res), blocks, iters, stream())), 5)
+        out["mfma_regs_" + name] = round(blocks * 4 * iters * 16 * 32768.0 / s / 1e12, 1)
+    # ---- the GEMM's reduction loop on C = A B^T, 8192 x 8192 x 4096
+    M = N = 8192
+    K = 4096
+    C = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    names = {0: "gemm_loop", 1: "gemm_loop_no_loads", 2: "gemm_loop_no_lds_reads", 3: "gemm_loop_no_mfma"}
+    for dname in ("random", "zeros"):
+        if dname == "random":
+            A = torch.randn(M + 256, K, generator=g, device="cuda").to(torch.bfloat16)
+            B = torch.randn(N + 256, K, generator=g, device="cuda").to(torch.bfloat16)
+        else:
+            A = torch.zeros(M + 256, K, dtype=torch.bfloat16, device="cuda")
+            B = torch.zeros(N + 256, K, dtype=torch.bfloat16, device="cuda")
+        for variant, name in names.items():
+            s = timed(lambda: call(L.symi_ceiling_gemm_loop(variant, ptr(A), ptr(B), ptr(C), M, N, K,
+                                                            A.numel(), B.numel(), stream())), args.steps)
+            out[f"{name}_{dname}"] = round(2.0 * M * N * K / s / 1e12, 1)   # MFMA-equivalent rate
+        del A, B
+    del C
+    # ---- the Adam step's streams on c2's shard (100.7 M parameters, 1.5 replicas per parameter)
+    n = 100663296
+    gr = torch.randn(n, generator=g, device="cuda")
+    w = torch.randn(n, generator=g, device="cuda")
+    m = torch.zeros(n, device="cuda")
+    v = torch.full((n,), 1e-4, device="cuda")
+    s0 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    s1 = torch.empty(n // 2, dtype=torch.bfloat16, device="cuda")
+    by = n * (16.0 + 12.0 + 3.0)
+    for layout, lname in ((0, "8_per_thread"), (1, "lane_contiguous_x1"), (2, "lane_contiguous_x2"), (4, "lane_contiguous_x4")):
+        for gs, gname in ((0, "one_pass"), (1, "grid_stride")):
+            s = timed(lambda: call(L.symi_ceiling_adam_streams(layout, ptr(gr), ptr(w), ptr(m), ptr(v), ptr(s0), ptr(s1),
+                                                               n, gs, stream())), args.steps)
+            out[f"adam_streams_{lname}_{gname}"] = round(by / s / 1e9, 1)
+    # ---- torch's own streaming kernels on the same buffers
+    out["torch_fill"] = round(4.0 * n / timed(lambda: w.fill_(1.0), args.steps) / 1e9, 1)
+    out["torch_copy"] = round(8.0 * n / timed(lambda: m.copy_(w), args.steps) / 1e9, 1)
+    out["torch_add"] = round(12.0 * n / timed(lambda: torch.add(w, gr, out=m), args.steps) / 1e9, 1)
+    print(json.dumps(out))
+
+
 def calibrate_copy():
     """A plain copy of known size, to scale the HBM counters: 8 copies of 1 GiB."""
     import torch
@@ -458,6 +542,10 @@ def main():
                          "tokens written and read back) instead of the *_active pair")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device copy (reference for the HBM traffic counters)")
+    ap.add_argument("--ceiling", action="store_true",
+                    help="run the microbenchmarks of what the part sustains (register-only MFMA, the "
+                         "GEMM loop with and without its ingredients, the Adam stream mix, torch fill/"
+                         "copy) instead of the benchmark; --steps = launches per figure")
     ap.add_argument("--extras", action="store_true",
                     help="time the router GEMM/backward and the per-slot replica gradient path on "
                          "--config instead of the benchmark")
@@ -473,6 +561,9 @@ def main():
         return
     if args.extras:
         extras(args)
+        return
+    if args.ceiling:
+        ceilings(args)
         return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share of the path; --gpus must be 1 "

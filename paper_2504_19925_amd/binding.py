@@ -88,7 +88,8 @@ class SymiAdam(ctypes.Structure):
 
 
 def lib_path():
-    return os.path.join(_HERE, "libsymi.so")
+    """The in-tree library; SYMI_LIB names another build of it (A/B measurements)."""
+    return os.environ.get("SYMI_LIB") or os.path.join(_HERE, "libsymi.so")
 
 
 def lib():

@@ -7,6 +7,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsymi.so")
+# microbenchmarks of the part's ceilings (bench.py --ceiling): a library of their own, so that
+# nothing of them is part of the product's ABI
+CEILINGS_LIB = os.path.join(HERE, "libsymi_ceilings.so")
 SOURCES = ["api.hip", "route.hip", "place.hip", "dispatch.hip", "gemm.hip", "adam.hip", "comm_plan.hip", "router.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -16,6 +19,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 def build(verbose: bool = True) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, "ceilings.hip"), "-o", CEILINGS_LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -180,11 +180,16 @@ __device__ __forceinline__ void tail_slices(int n_tiles, int cus, int K, int& fu
   }
 }
 
-template <int MODE>
-__global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
+// One tile of one product.  MI = 32-row blocks per wavefront: 4 for the 256-row tile (each of the
+// 2 x 2 wavefronts 128 x 128), 2 for the 128-row tile that holds the ragged end of a slot when
+// it has at most 128 rows (each wavefront 64 x 128: half the MFMAs, and the two wavefronts whose
+// 64-row band of the left operand lies beyond the tile load nothing of it).
+template <int MODE, int MI>
+__device__ __forceinline__ void gemm_tile(const GemmParams& p, uint16_t* const smem, const int row0,
+                                          const int row1, const int group, const int kbeg, const int K,
+                                          const int bx, const int nsl, const int kofs, const int pslot) {
   // [left stage 0 | left stage 1 | right stage 0 | right stage 1], 32 KB each: the two
   // stages of an operand differ by an immediate offset of the LDS read instructions
-  __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * BM * BK + 2 * BN * BK];
   uint16_t* const sA0 = smem;
   uint16_t* const sA1 = smem + BM * BK;
   uint16_t* const sB0 = smem + 2 * BM * BK;
@@ -195,52 +200,10 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   constexpr bool VARM = MODE <= BWD_DX;
   constexpr bool A_KC = VARM;                       // left operand reduction-contiguous
   constexpr bool B_KC = MODE == FWD1 || MODE == FWD2;
-
-  int row0, row1, group, kbeg = 0, K, bx = blockIdx.x;
-  // this workgroup reduces slice zsl of nsl, starting at reduction index kofs; if nsl > 1 its
-  // accumulators go to partial slot pslot
-  int nsl = 1, zsl = 0, kofs = 0, pslot = 0;
-  if (VARM) {
-    // tiles in launch order (column index fastest); the last round's tiles may be sliced
-    const int ntx = gridDim.x;
-    const int n_tiles = p.tile_map[0] * ntx;
-    const int b = blockIdx.y * ntx + blockIdx.x;
-    int full = n_tiles, sl = 1;
-    if ((MODE == FWD2 || MODE == BWD_DX) && p.partials) tail_slices(n_tiles, p.cus, p.K, full, sl);
-    int tile = b;
-    if (b >= full) {
-      tile = full + (b - full) / sl;
-      zsl = (b - full) % sl;
-      nsl = sl;
-    }
-    if (tile >= n_tiles) return;
-    const int mt = tile / ntx;
-    bx = tile - mt * ntx;
-    row0 = p.tile_map[4 + 4 * mt];
-    row1 = p.tile_map[4 + 4 * mt + 1];
-    group = p.tile_map[4 + 4 * mt + 2];
-    K = p.K;
-    if (nsl > 1) {
-      const int nk_all = (p.K + BK - 1) / BK;
-      const int len = ((nk_all + nsl - 1) / nsl + 1) / 2 * 2 * BK;   // whole pairs of steps
-      kofs = zsl * len;
-      K = max(0, min(len, p.K - kofs));
-      pslot = (tile - full) * nsl + zsl;
-    }
-  } else {
-    // classes in order of decreasing row count: the long reductions start first and the
-    // short (or empty, store-only) tiles fill in behind them
-    group = p.per_slot ? blockIdx.z : p.class_order[blockIdx.z];
-    row0 = blockIdx.y * BM;
-    row1 = min(p.M, row0 + BM);
-    if (p.per_slot) {   // the rows of one replica slot
-      kbeg = p.slot_offsets[group];
-      K = p.slot_offsets[group + 1] - kbeg;
-    } else {            // the rows of all replica slots of a class
-      kbeg = p.slot_offsets[p.first_slot[group]];
-      K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
-    }
-  }
+  constexpr int WROWS = 32 * MI;                    // output rows of one wavefront
+  static_assert(MI == 4 || (MI == 2 && VARM), "the 128-row tile serves the variable-row products");
+  // a wavefront whose 64 rows of the left tile lie beyond a 128-row tile loads nothing of it
+  const bool skip_left = MI == 2 && wave >= 2;
   // FWD1: a tile holds 128 hidden units; every 64 tile columns are 32 gate columns
   // followed by the 32 up columns of the same hidden units.
   const int n0 = bx * (MODE == FWD1 ? BN / 2 : BN);
@@ -334,6 +297,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   auto dma_one = [&](uint16_t* sA, uint16_t* sB, int k0, int q, auto partial) {
     const int j = q >> 1;
     const bool right = q & 1;
+    if (MI == 2 && !right && skip_left) return;
     const bool kcontig = right ? B_KC : A_KC;
     const uint16_t* base = right ? b_base : a_base;
     const long long ld = right ? ldb : lda;
@@ -364,43 +328,47 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   for (int x = 0; x < 4; ++x) {
     const int kc = r31 * BK + (((2 * x + (lane >> 5)) ^ ((r31 >> 1) & 7)) * 8);             // x = sub-step
     const int ksc = ks_row + (((4 * x + 2 * (g4 & 1) + ((jj & 3) >> 1)) ^ ks_h2) * 8) + 4 * (jj & 1);  // x = block
-    adA[x] = (unsigned)(size_t)SYMI_LPTR(sA0) + 2u * (unsigned)(A_KC ? wm * 128 * BK + kc : wm * 128 + ksc);
+    adA[x] = (unsigned)(size_t)SYMI_LPTR(sA0) + 2u * (unsigned)(A_KC ? wm * WROWS * BK + kc : wm * WROWS + ksc);
     adB[x] = (unsigned)(size_t)SYMI_LPTR(sB0) + 2u * (unsigned)(B_KC ? wn * 128 * BK + kc : wn * 128 + ksc);
   }
   // All LDS reads are inline assembly: the compiler cannot tell the stage being read from the
   // one being filled by direct-to-LDS loads and would wait for the prefetch before every
   // read.  Completion is awaited by hand (lgkmcnt(0)) at the start of the phase that uses them.
-  bf16x8 fa[2][4], fb[2][4];   // two register sets: one feeds the MFMAs, the other is being filled
-  auto load_frags = [&](auto bufc, auto stagec, auto ksc) {
+  bf16x8 fa[2][MI], fb[2][4];   // two register sets: one feeds the MFMAs, the other is being filled
+  // half = 0 / 1: fragments 0, 1 / 2, 3 of both operands; 2: all of them
+  auto load_frags = [&](auto bufc, auto stagec, auto ksc, auto halfc) {
     constexpr int bu = decltype(bufc)::value, S = decltype(stagec)::value, KS = decltype(ksc)::value;
+    constexpr int HF = decltype(halfc)::value;
     constexpr int SO = S * BM * BK * 2;   // stage offset in bytes
-    if (A_KC) {
-      fa[bu][0] = lds_read_b128<SO + 0 * 4096>(adA[KS]);
-      fa[bu][1] = lds_read_b128<SO + 1 * 4096>(adA[KS]);
-      fa[bu][2] = lds_read_b128<SO + 2 * 4096>(adA[KS]);
-      fa[bu][3] = lds_read_b128<SO + 3 * 4096>(adA[KS]);
-    } else {
-      fa[bu][0] = lds_read_tr<SO + KS * 8192>(adA[0]);
-      fa[bu][1] = lds_read_tr<SO + KS * 8192>(adA[1]);
-      fa[bu][2] = lds_read_tr<SO + KS * 8192>(adA[2]);
-      fa[bu][3] = lds_read_tr<SO + KS * 8192>(adA[3]);
+    constexpr bool LO = HF != 1, HI = HF != 0;
+#pragma unroll
+    for (int x = 0; x < MI; ++x) {
+      if (!(x < MI / 2 ? LO : HI)) continue;
+      if (A_KC) {
+        if (x == 0) fa[bu][0] = lds_read_b128<SO + 0 * 4096>(adA[KS]);
+        if (x == 1) fa[bu][1] = lds_read_b128<SO + 1 * 4096>(adA[KS]);
+        if (x == 2) fa[bu][x] = lds_read_b128<SO + 2 * 4096>(adA[KS]);
+        if (x == 3) fa[bu][x] = lds_read_b128<SO + 3 * 4096>(adA[KS]);
+      } else {
+        fa[bu][x] = lds_read_tr<SO + KS * 8192>(adA[x]);
+      }
     }
     if (B_KC) {
-      fb[bu][0] = lds_read_b128<SO + 0 * 4096>(adB[KS]);
-      fb[bu][1] = lds_read_b128<SO + 1 * 4096>(adB[KS]);
-      fb[bu][2] = lds_read_b128<SO + 2 * 4096>(adB[KS]);
-      fb[bu][3] = lds_read_b128<SO + 3 * 4096>(adB[KS]);
+      if (LO) fb[bu][0] = lds_read_b128<SO + 0 * 4096>(adB[KS]);
+      if (LO) fb[bu][1] = lds_read_b128<SO + 1 * 4096>(adB[KS]);
+      if (HI) fb[bu][2] = lds_read_b128<SO + 2 * 4096>(adB[KS]);
+      if (HI) fb[bu][3] = lds_read_b128<SO + 3 * 4096>(adB[KS]);
     } else {
-      fb[bu][0] = lds_read_tr<SO + KS * 8192>(adB[0]);
-      fb[bu][1] = lds_read_tr<SO + KS * 8192>(adB[1]);
-      fb[bu][2] = lds_read_tr<SO + KS * 8192>(adB[2]);
-      fb[bu][3] = lds_read_tr<SO + KS * 8192>(adB[3]);
+      if (LO) fb[bu][0] = lds_read_tr<SO + KS * 8192>(adB[0]);
+      if (LO) fb[bu][1] = lds_read_tr<SO + KS * 8192>(adB[1]);
+      if (HI) fb[bu][2] = lds_read_tr<SO + KS * 8192>(adB[2]);
+      if (HI) fb[bu][3] = lds_read_tr<SO + KS * 8192>(adB[3]);
     }
   };
 
-  floatx16 acc[4][4];
+  floatx16 acc[MI][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -429,24 +397,29 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
       __builtin_amdgcn_s_barrier();       // ... so has everybody's, and stage S is free
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (KS == 3) load_frags(IC<bu ^ 1>{}, IC<S ^ 1>{}, IC<0>{});
-    else load_frags(IC<bu ^ 1>{}, IC<S>{}, IC<(KS + 1) & 3>{});
-    __builtin_amdgcn_sched_barrier(0);
     if (decltype(partial)::value && (KS == 3 || KS == 0)) {
       // keep the address arithmetic of these loads inside the phase (not hoisted into registers)
       asm volatile("" : "+v"(kc_row), "+v"(kc_c0), "+v"(ks_kb), "+v"(ks_c0), "+v"(f1_row));
     }
+    constexpr int LPI = 8 / MI;   // loads issued behind each MFMA group of a phase that loads
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < MI; ++i) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[bu][j], fa[bu][i], acc[i][j], 0, 0, 0);
-      if (KS == 3) {
-        dma_one(cA, cB, (step + 2) * BK, 2 * i, partial);
-        dma_one(cA, cB, (step + 2) * BK, 2 * i + 1, partial);
-      } else if (KS == 0) {
-        dma_one(oA, oB, (step + 1) * BK, 8 + 2 * i, partial);
-        dma_one(oA, oB, (step + 1) * BK, 8 + 2 * i + 1, partial);
+      // the next phase's fragments, half of them behind each of the first two MFMA groups: the
+      // matrix pipe has work queued while the reads issue, and they still have half a phase to land
+      if (i == 0) {
+        if (KS == 3) load_frags(IC<bu ^ 1>{}, IC<S ^ 1>{}, IC<0>{}, IC<0>{});
+        else load_frags(IC<bu ^ 1>{}, IC<S>{}, IC<(KS + 1) & 3>{}, IC<0>{});
+      } else if (i == 1) {
+        if (KS == 3) load_frags(IC<bu ^ 1>{}, IC<S ^ 1>{}, IC<0>{}, IC<1>{});
+        else load_frags(IC<bu ^ 1>{}, IC<S>{}, IC<(KS + 1) & 3>{}, IC<1>{});
+      }
+#pragma unroll
+      for (int u = 0; u < LPI; ++u) {
+        if (KS == 3) dma_one(cA, cB, (step + 2) * BK, LPI * i + u, partial);
+        else if (KS == 0) dma_one(oA, oB, (step + 1) * BK, 8 + LPI * i + u, partial);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -472,9 +445,11 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) dma_one(sA1, sB1, BK, q, std::true_type{});
   }
-  __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8): step 0 has landed, the half of step 1 may still fly
+  // step 0 has landed, the half of step 1 may still fly: 8 loads, or the 4 of a wavefront that
+  // skips the left operand (the others then wait for 4 loads of step 1 as well)
+  if (MI == 4) __builtin_amdgcn_s_waitcnt(0x0F78); else __builtin_amdgcn_s_waitcnt(0x0F74);
   __builtin_amdgcn_s_barrier();
-  load_frags(IC<0>{}, IC<0>{}, IC<0>{});
+  load_frags(IC<0>{}, IC<0>{}, IC<0>{}, IC<2>{});
   // always pairs of steps: for an odd step count the second stage holds the zeros of the
   // dummy loads and adds nothing (a mid-loop exit would cost more than the idle step).  A
   // pair starting at step t loads steps up to t + 3.
@@ -503,8 +478,8 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   // a slice stores its accumulators the way a weight gradient is stored: fp32, pitch 256
   const bool to_partial = (MODE == FWD2 || MODE == BWD_DX) && nsl > 1;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int rbase = row0 + wm * 128 + i * 32;   // first output row of this block
+  for (int i = 0; i < MI; ++i) {
+    const int rbase = row0 + wm * WROWS + i * 32;   // first output row of this block
     if (MODE == FWD1) {
       uint16_t* const su = stg;
       uint16_t* const sv = stg + 32 * LDH;
@@ -559,7 +534,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
       auto load_uv = [&](int blk, uint4 (&uu)[8], uint4 (&vv)[8]) {
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
-          const int row = row0 + wm * 128 + blk * 32 + it * 4 + (lane >> 4);
+          const int row = row0 + wm * WROWS + blk * 32 + it * 4 + (lane >> 4);
           if (row < row1 && col < p.N) {
             const long long o = (long long)row * 2 * p.f + col;
             uu[it] = *reinterpret_cast<const uint4*>(UVi + o);
@@ -568,7 +543,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
         }
       };
       if (i == 0) load_uv(0, uvu[0], uvv[0]);
-      if (i + 1 < 4) load_uv(i + 1, uvu[(i + 1) & 1], uvv[(i + 1) & 1]);
+      if (i + 1 < MI) load_uv(i + 1, uvu[(i + 1) & 1], uvv[(i + 1) & 1]);
 #pragma unroll
       for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -634,7 +609,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
               make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
       __builtin_amdgcn_s_waitcnt(0xC07F);
       if (VARM) {   // a slice's partial tile
-        float* Co = p.partials + (size_t)pslot * (BM * BN) + (wm * 128 + i * 32) * BN + wn * 128 + (lane & 31) * 4;
+        float* Co = p.partials + (size_t)pslot * (BM * BN) + (wm * WROWS + i * 32) * BN + wn * 128 + (lane & 31) * 4;
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
           const int rr = it * 2 + (lane >> 5);
@@ -656,6 +631,65 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_sched_barrier(0);
   }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
+  __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * BM * BK + 2 * BN * BK];
+  constexpr bool VARM = MODE <= BWD_DX;
+  int row0, row1, group, kbeg = 0, K, bx = blockIdx.x;
+  // this workgroup reduces slice zsl of nsl, starting at reduction index kofs; if nsl > 1 its
+  // accumulators go to partial slot pslot
+  int nsl = 1, zsl = 0, kofs = 0, pslot = 0;
+  if (VARM) {
+    // tiles in launch order (column index fastest); the last round's tiles may be sliced
+    const int ntx = gridDim.x;
+    const int n_tiles = p.tile_map[0] * ntx;
+    const int b = blockIdx.y * ntx + blockIdx.x;
+    int full = n_tiles, sl = 1;
+    if ((MODE == FWD2 || MODE == BWD_DX) && p.partials) tail_slices(n_tiles, p.cus, p.K, full, sl);
+    int tile = b;
+    if (b >= full) {
+      tile = full + (b - full) / sl;
+      zsl = (b - full) % sl;
+      nsl = sl;
+    }
+    if (tile >= n_tiles) return;
+    const int mt = tile / ntx;
+    bx = tile - mt * ntx;
+    row0 = p.tile_map[4 + 4 * mt];
+    row1 = p.tile_map[4 + 4 * mt + 1];
+    group = p.tile_map[4 + 4 * mt + 2];
+    K = p.K;
+    if (nsl > 1) {
+      const int nk_all = (p.K + BK - 1) / BK;
+      const int len = ((nk_all + nsl - 1) / nsl + 1) / 2 * 2 * BK;   // whole pairs of steps
+      kofs = zsl * len;
+      K = max(0, min(len, p.K - kofs));
+      pslot = (tile - full) * nsl + zsl;
+    }
+  } else {
+    // classes in order of decreasing row count: the long reductions start first and the
+    // short (or empty, store-only) tiles fill in behind them
+    group = p.per_slot ? blockIdx.z : p.class_order[blockIdx.z];
+    row0 = blockIdx.y * BM;
+    row1 = min(p.M, row0 + BM);
+    if (p.per_slot) {   // the rows of one replica slot
+      kbeg = p.slot_offsets[group];
+      K = p.slot_offsets[group + 1] - kbeg;
+    } else {            // the rows of all replica slots of a class
+      kbeg = p.slot_offsets[p.first_slot[group]];
+      K = p.slot_offsets[p.first_slot[group + 1]] - kbeg;
+    }
+  }
+  if constexpr (VARM) {
+    // the ragged end of a slot: at most 128 rows take the half-height tile
+    if (__builtin_amdgcn_readfirstlane(row1 - row0) <= BM / 2) {
+      gemm_tile<MODE, 2>(p, smem, row0, row1, group, kbeg, K, bx, nsl, kofs, pslot);
+      return;
+    }
+  }
+  gemm_tile<MODE, 4>(p, smem, row0, row1, group, kbeg, K, bx, nsl, kofs, pslot);
 }
 
 // ---------------------------------------------------------------- sum of reduction slices
