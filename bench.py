@@ -230,6 +230,10 @@ def ceilings(args):
             s = timed(lambda: call(L.symi_ceiling_gemm_loop(variant, ptr(A), ptr(B), ptr(C), M, N, K,
                                                             A.numel(), B.numel(), stream())), args.steps)
             out[f"{name}_{dname}"] = round(2.0 * M * N * K / s / 1e12, 1)   # MFMA-equivalent rate
+        # the vendor library's kernel for the same product (torch.matmul -> hipBLASLt), and for a
+        # deeper one: what a plain bf16 GEMM reaches on this part with this data
+        s = timed(lambda: torch.matmul(A[:M], B[:N].t(), out=C), args.steps)
+        out[f"vendor_gemm_8192x8192x4096_{dname}"] = round(2.0 * M * N * K / s / 1e12, 1)
         del A, B
     del C
     # ---- the Adam step's streams on c2's shard (100.7 M parameters, 1.5 replicas per parameter)

@@ -726,10 +726,15 @@ __global__ __launch_bounds__(256) void slice_sum_kernel(GemmParams p, int ntx) {
 // ---------------------------------------------------------------- fp32 FMA twin
 // Same six products for fp32 activations/weights: 64x64 output tile, 16-deep reduction
 // steps, each thread a 4x4 micro-tile, plain FMAs in fp32.
-constexpr int FB = 64, FK = 16;
+// The weight gradients of a small batch are few tiles with long reductions: they also come with
+// a 32x32 tile (2x2 micro-tile) that makes four times as many workgroups.
+constexpr int FK = 16;
 
-template <int MODE>
+template <int MODE, int FB>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
+  constexpr int MT = FB / 16;             // micro-tile edge of a thread
+  constexpr int NH = FB * FK / 256;       // elements per operand a thread carries per step
+  static_assert(FB == 64 || (FB == 32 && MODE >= WGRAD2), "32x32 tiles serve the weight gradients");
   __shared__ float As[FK][FB + 4];
   __shared__ float Bs[FK][FB + 4];
   const int tid = threadIdx.x;
@@ -793,15 +798,15 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
   };
   constexpr bool A_KC = VARM, B_KC = MODE == FWD1 || MODE == FWD2;
 
-  float acc[4][4] = {};
-  const int ty = tid >> 4, tx = tid & 15;  // rows ty*4.., cols tx + 16*c (FWD1 pairs gate/up)
+  float acc[MT][MT] = {};
+  const int ty = tid >> 4, tx = tid & 15;  // rows ty*MT.., cols tx + 16*c (FWD1 pairs gate/up)
   // each thread carries 4 + 4 elements of a step from memory to LDS; the elements of the next
   // step are fetched into registers before the current step's FMAs, so their latency hides
   // behind them.  Operands are walked along their contiguous index for coalescing.
-  float na[4], nb[4];
+  float na[NH], nb[NH];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
+    for (int h = 0; h < NH; ++h) {
       const int e = tid + 256 * h;
       const int ai = A_KC ? e / FK : e % FB, ak = A_KC ? e % FK : e / FB;
       na[h] = a_at(ai, k0 + ak);
@@ -812,7 +817,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
   if (K > 0) fetch(0);
   for (int k0 = 0; k0 < K; k0 += FK) {
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
+    for (int h = 0; h < NH; ++h) {
       const int e = tid + 256 * h;
       const int ai = A_KC ? e / FK : e % FB, ak = A_KC ? e % FK : e / FB;
       As[ak][ai] = na[h];
@@ -823,31 +828,31 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
     if (k0 + FK < K) fetch(k0 + FK);
     // two-level summation: each 16-deep partial sum is formed on its own and then added,
     // which keeps the rounding error of long reductions (weight gradients) near sqrt(K/16)
-    float part[4][4] = {};
+    float part[MT][MT] = {};
 #pragma unroll
     for (int k = 0; k < FK; ++k) {
-      float a[4], b[4];
+      float a[MT], b[MT];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+      for (int i = 0; i < MT; ++i) a[i] = As[k][ty * MT + i];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) b[c] = Bs[k][tx + 16 * c];
+      for (int c = 0; c < MT; ++c) b[c] = Bs[k][tx + 16 * c];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) part[i][c] = fmaf(a[i], b[c], part[i][c]);
+        for (int c = 0; c < MT; ++c) part[i][c] = fmaf(a[i], b[c], part[i][c]);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MT; ++i)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) acc[i][c] += part[i][c];
+      for (int c = 0; c < MT; ++c) acc[i][c] += part[i][c];
     __syncthreads();
   }
 
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = row0 + ty * 4 + i;
+  for (int i = 0; i < MT; ++i) {
+    const int row = row0 + ty * MT + i;
     if (row >= row1) continue;
-    if (MODE == FWD1) {
+    if constexpr (MODE == FWD1) {
       // columns tx, tx+16 are gate of hidden units n0+tx, n0+tx+16; tx+32, tx+48 their up
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
@@ -861,7 +866,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
       }
     } else {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < MT; ++c) {
         const int col = n0 + tx + 16 * c;
         if (col >= p.N) continue;
         const float x = acc[i][c];
@@ -897,9 +902,19 @@ static void launch_gemm(const symi_ctx* ctx, const GemmParams& p, int n_cols, in
     if (may_slice)   // the sliced round holds at most cus / 2 tiles
       SYMI_TIMED(ctx, K_SLICE_SUM, st, (slice_sum_kernel<<<dim3(BM / 16, std::max(1, p.cus / 2)), 256, 0, st>>>(p, ntx)));
   } else {
+    constexpr int FB = 64;
     const int bn = MODE == FWD1 ? FB / 2 : FB;
-    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 4 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : (p.per_slot ? cfg->S_tot : cfg->E));
-    SYMI_TIMED(ctx, K_GEMM_FWD1 + MODE, st, (gemm_f32_kernel<MODE><<<grid, 256, 0, st>>>(p)));
+    const int groups = p.per_slot ? cfg->S_tot : cfg->E;
+    if constexpr (MODE >= WGRAD2) {
+      // few tiles (a small batch leaves most of them to a handful of classes): quarter tiles
+      if ((long long)cdiv(n_cols, FB) * cdiv(p.M, FB) * groups < 4LL * ctx->cus) {
+        dim3 grid(cdiv(n_cols, 32), cdiv(p.M, 32), groups);
+        SYMI_TIMED(ctx, K_GEMM_FWD1 + MODE, st, (gemm_f32_kernel<MODE, 32><<<grid, 256, 0, st>>>(p)));
+        return;
+      }
+    }
+    dim3 grid(cdiv(n_cols, bn), MODE <= BWD_DX ? 4 * max_mtiles : cdiv(p.M, FB), MODE <= BWD_DX ? 1 : groups);
+    SYMI_TIMED(ctx, K_GEMM_FWD1 + MODE, st, (gemm_f32_kernel<MODE, 64><<<grid, 256, 0, st>>>(p)));
   }
 }
 

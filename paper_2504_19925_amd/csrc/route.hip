@@ -64,27 +64,48 @@ __device__ __forceinline__ void row_stats(const float (&z)[NV * 4], int E, int G
   zsum = s;
 }
 
-template <int NV>
+// Order-preserving integer image of a float (an involution): a > b  <=>  key(a) > key(b) for all
+// non-NaN floats, -inf included.  INT_MIN is no float's key: it marks what can never be chosen
+// (a column beyond E, a NaN).
+__device__ __forceinline__ int order_key(float z) {
+  const int i = __float_as_int(z);
+  return i ^ ((i >> 31) & 0x7fffffff);
+}
+constexpr int KEY_NONE = INT_MIN;
+
+// G lanes share a token's row, NV float4 pieces each (both compile-time: the column of a lane's
+// c-th value is then a constant plus 4 g).  Each of the k rounds scans the lane's own values in
+// increasing column order with a strict comparison (so the lowest column wins ties inside a
+// lane without comparing columns), skips the values retired in earlier rounds by a bit mask, and
+// settles the winner across the group by a butterfly over (key, column) pairs.
+template <int G, int NV>
 __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
     const float* __restrict__ logits, int32_t* __restrict__ idx, float* __restrict__ gate,
-    int32_t* __restrict__ hist, int T, int E, int k, int G, int renorm) {
+    int32_t* __restrict__ hist, int T, int E, int k, int renorm) {
   extern __shared__ int32_t hist_s[];
   for (int i = threadIdx.x; i < E; i += ROUTE_THREADS) hist_s[i] = 0;
   __syncthreads();
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int g = lane & (G - 1), sub = lane / G, tpw = 64 / G;
-  const int tpb = (ROUTE_THREADS / 64) * tpw;
+  const int g = lane & (G - 1), sub = lane / G;
+  constexpr int tpw = 64 / G;
+  constexpr int tpb = (ROUTE_THREADS / 64) * tpw;
+  constexpr int NVAL = NV * 4;
+  auto col_of = [&](int c) { return ((c >> 2) * G + g) * 4 + (c & 3); };
 
   for (long long t0 = (long long)blockIdx.x * tpb; t0 < T; t0 += (long long)gridDim.x * tpb) {
     const long long t = t0 + wave * tpw + sub;
     const bool valid = t < T;
-    float z[NV * 4];
+    float z[NVAL];
     load_row<NV>(logits + (valid ? t : 0) * E, E, G, g, valid, z);
     float zmax, zsum;
     row_stats<NV>(z, E, G, g, zmax, zsum);
+    int key[NVAL];
+#pragma unroll
+    for (int c = 0; c < NVAL; ++c)
+      key[c] = (col_of(c) < E && z[c] == z[c]) ? order_key(z[c] + 0.f) : KEY_NONE;   // -0 counts as +0
 
-    unsigned taken = 0;
+    unsigned taken = 0;   // NVAL <= 32 values per lane
     float pj[MAX_K];
     int ij[MAX_K];
     float psum = 0.f;
@@ -93,23 +114,27 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
       pj[j] = 0.f;
       ij[j] = 0;
       if (j < k) {
-        float bv = -INFINITY;
-        int bi = INT_MAX;
+        int bk = KEY_NONE, bc = 0;
 #pragma unroll
-        for (int c = 0; c < NV * 4; ++c) {
-          const int col = ((c >> 2) * G + g) * 4 + (c & 3);
-          const bool ok = col < E && !((taken >> c) & 1u);
-          if (ok && (z[c] > bv || (z[c] == bv && col < bi))) { bv = z[c]; bi = col; }
+        for (int c = 0; c < NVAL; ++c) {
+          const bool better = !((taken >> c) & 1u) && key[c] > bk;
+          bk = better ? key[c] : bk;
+          bc = better ? c : bc;
         }
+        int bi = bk == KEY_NONE ? INT_MAX : col_of(bc);
+        const int mine = bi;
+#pragma unroll
         for (int m = G >> 1; m >= 1; m >>= 1) {
-          const float ov = __shfl_xor(bv, m, 64);
+          const int ok = __shfl_xor(bk, m, 64);
           const int oi = __shfl_xor(bi, m, 64);
-          if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+          const bool other = ok > bk || (ok == bk && oi < bi);
+          bk = other ? ok : bk;
+          bi = other ? oi : bi;
         }
         // the lane that owns the winner retires it
-        const int vec = bi >> 2;
-        if (bi != INT_MAX && (vec & (G - 1)) == g) taken |= 1u << (((vec / G) << 2) | (bi & 3));
-        pj[j] = expf(bv - zmax) / zsum;
+        if (bi != INT_MAX && bi == mine) taken |= 1u << bc;
+        const float bv = __int_as_float(bk ^ ((bk >> 31) & 0x7fffffff));
+        pj[j] = bi != INT_MAX ? expf(bv - zmax) / zsum : 0.f;
         ij[j] = bi;
         psum += pj[j];
       }
@@ -243,14 +268,20 @@ extern "C" int symi_route(const symi_ctx* ctx, const float* logits, int32_t* idx
     route_fwd_shape(E, cfg->T, G, NV);
     const int grid = route_grid(cfg->T, G);
     const size_t sh = (size_t)E * sizeof(int32_t);
-    if (NV == 1)
-      SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<1><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
-    else if (NV == 2)
-      SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<2><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
-    else if (NV == 4)
-      SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<4><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
-    else
-      SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<8><<<grid, ROUTE_THREADS, sh, st>>>(logits, idx, gate, hist, cfg->T, E, cfg->k, G, cfg->renorm)));
+#define SYMI_ROUTE_CASE(GG, NN)                                                                  \
+  case GG * 16 + NN:                                                                             \
+    SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<GG, NN><<<grid, ROUTE_THREADS, sh, st>>>(          \
+        logits, idx, gate, hist, cfg->T, E, cfg->k, cfg->renorm)));                              \
+    break;
+#define SYMI_ROUTE_G(GG) SYMI_ROUTE_CASE(GG, 1) SYMI_ROUTE_CASE(GG, 2) SYMI_ROUTE_CASE(GG, 4) SYMI_ROUTE_CASE(GG, 8)
+    switch (G * 16 + NV) {
+      SYMI_ROUTE_G(1) SYMI_ROUTE_G(2) SYMI_ROUTE_G(4) SYMI_ROUTE_G(8) SYMI_ROUTE_G(16) SYMI_ROUTE_G(32) SYMI_ROUTE_G(64)
+      default:
+        set_error("symi_route: no kernel for %d lanes x %d pieces per token", G, NV);
+        return SYMI_EUNSUPPORTED;
+    }
+#undef SYMI_ROUTE_G
+#undef SYMI_ROUTE_CASE
   }
   SYMI_LAUNCH_CHECK("symi_route");
   return SYMI_OK;
