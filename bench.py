@@ -491,6 +491,7 @@ def cpu_baseline(c):
     hist_prev = np.zeros(c.E, dtype=np.int64)
     t_layer = t_adam = 0.0
     n_it = 0
+    stages = {}
     # whole iterations of the workload until about 10 s of oracle time are spent (at most 3)
     for it in range(min(max(c.iters, 1), 3)):
         Xt = wl.make_tokens(c, it, dev)
@@ -498,22 +499,27 @@ def cpu_baseline(c):
         z = wl.make_logits(c, it, dev, tokens=Xt)[:Ts].cpu().numpy()
         dY = wl.make_upstream_grad(c, it, dev)[:Ts].float().cpu().numpy()
         del Xt
-        t0 = time.perf_counter()
-        idx, gate, hist = O.route(z, c.k, True)
-        counts, placement, first = O.place(hist_prev, c.S_tot)
-        O.dispatch(idx, counts, first)
-        O.moe_forward(X, idx, gate, W1, W2)
-        dX, dW1, dW2, dgate = O.moe_backward(X, idx, gate, W1, W2, dY)
-        O.route_backward(z, idx, gate, dgate, True)
-        n_counts, n_place, n_first = O.place(hist, c.S_tot)
-        t_layer += time.perf_counter() - t0
+        def stage(name, fn):
+            t0 = time.perf_counter()
+            r = fn()
+            dt = time.perf_counter() - t0
+            stages[name] = stages.get(name, 0.0) + dt
+            return r, dt
+        (idx, gate, hist), d1 = stage("route", lambda: O.route(z, c.k, True))
+        (counts, placement, first), d2 = stage("place", lambda: O.place(hist_prev, c.S_tot))
+        _, d3 = stage("dispatch", lambda: O.dispatch(idx, counts, first))
+        _, d4 = stage("layer_fwd", lambda: O.moe_forward(X, idx, gate, W1, W2))
+        (dX, dW1, dW2, dgate), d5 = stage("layer_bwd", lambda: O.moe_backward(X, idx, gate, W1, W2, dY))
+        _, d6 = stage("route_bwd", lambda: O.route_backward(z, idx, gate, dgate, True))
+        (n_counts, n_place, n_first), d7 = stage("place_next", lambda: O.place(hist, c.S_tot))
+        t_layer += d1 + d2 + d3 + d4 + d5 + d6 + d7
         sub_place = np.array([e for e in n_place if e < Es], dtype=np.int32)
         W1s = np.zeros((len(sub_place),) + W1.shape[1:], np.float32)
         W2s = np.zeros((len(sub_place),) + W2.shape[1:], np.float32)
-        t0 = time.perf_counter()
-        O.adam_to_replicas(dW1[:Es], dW2[:Es], flat, np.zeros_like(flat), np.zeros_like(flat), sub_place,
-                           c.N, 0, hp, c.dtype == "bf16", W1s, W2s)
-        t_adam += time.perf_counter() - t0
+        _, d8 = stage("adam_to_replicas", lambda: O.adam_to_replicas(
+            dW1[:Es], dW2[:Es], flat, np.zeros_like(flat), np.zeros_like(flat), sub_place, c.N, 0, hp,
+            c.dtype == "bf16", W1s, W2s))
+        t_adam += d8
         del dX, dW1, dW2, W1s, W2s
         hist_prev = hist
         n_it += 1
@@ -521,7 +527,11 @@ def cpu_baseline(c):
             break
 
     est_step = (t_layer * (c.T / Ts) + t_adam * (c.E / Es)) / n_it
+    # the oracle's stages beside the GPU's: seconds per full step (sample scaled as above)
+    scale = {"adam_to_replicas": c.E / Es, "place": 1.0, "place_next": 1.0}     # the others grow with the tokens
+    per_stage = {k: round(v / n_it * scale.get(k, c.T / Ts), 4) for k, v in stages.items()}
     return {"value": round(c.T / est_step, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "stage_seconds_per_step": per_stage,
             "sample": f"{n_it} iteration(s): layer fwd+bwd+routing on the first {Ts} of {c.T} tokens "
                       f"({t_layer:.2f} s), Adam+replica write on {Es} of {c.E} classes' shard ({t_adam:.2f} s); "
                       f"scaled linearly to one full step ({est_step:.1f} s)"}
