@@ -286,31 +286,50 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, uint16_t* const s
     krel = ks_kb + 2 * j;
     return (unsigned)((ks_kb + 2 * j) * ld + (c * 8 < lim ? c : 0) * 8);
   };
+  // The main loop's loads take the cheapest form the instruction has: a scalar base (operand +
+  // reduction step), a 32-bit per-lane byte offset from a register and an immediate, with the
+  // LDS base (M0) written once per operand and stage: the 8 instructions of an operand write 8
+  // consecutive KB, reached from an M0 in their middle through immediates of -4 .. +3 KB, which
+  // the per-lane offset takes back out of the global address (the scalar base sits 4 KB low so
+  // that the offset stays positive).  Measured in the loop's microbenchmark: an M0 write in front
+  // of every load and a 64-bit vector add for its address cost 26-36 cycles of MFMA issue per
+  // load, this form 4-8 (a 64-deep step 2750 -> 2340 cycles).  All direct-to-LDS loads of this
+  // kernel are inline assembly, so that nothing else ever writes M0.
   unsigned voA[8], voB[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     int unused;
-    voA[j] = lane_off(false, j, unused);
-    voB[j] = lane_off(true, j, unused);
+    voA[j] = lane_off(false, j, unused) * 2u + 4096u - (unsigned)((j - 4) * 1024);
+    voB[j] = lane_off(true, j, unused) * 2u + 4096u - (unsigned)((j - 4) * 1024);
   }
-  // q = 0..15: even = left operand, odd = right operand, instruction j = q/2
-  auto dma_one = [&](uint16_t* sA, uint16_t* sB, int k0, int q, auto partial) {
-    const int j = q >> 1;
-    const bool right = q & 1;
+  auto set_m0 = [&](unsigned lds_byte_addr) {
+    asm volatile("s_mov_b32 m0, %0" ::"s"(lds_byte_addr) : "memory");
+  };
+  auto load_fast = [&](auto jc, unsigned voff, const void* sbase) {
+    constexpr int J = decltype(jc)::value;
+    asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(sbase), "n"((J - 4) * 1024) : "memory");
+  };
+  // q = 0..7: instruction j = q of the left operand, q = 8..15: instruction j = q - 8 of the right one
+  auto dma_one = [&](uint16_t* sA, uint16_t* sB, int k0, auto qc, auto partial) {
+    constexpr int Q = decltype(qc)::value;
+    constexpr int j = Q & 7;
+    constexpr bool right = Q >= 8;
     if (MI == 2 && !right && skip_left) return;
     const bool kcontig = right ? B_KC : A_KC;
     const uint16_t* base = right ? b_base : a_base;
     const long long ld = right ? ldb : lda;
     const uint16_t* sbase = kcontig ? base + k0 : base + (long long)k0 * ld;   // wave-uniform
-    const uint16_t* src;
+    const unsigned lds0 = (unsigned)(size_t)SYMI_LPTR((right ? sB : sA) + wdst);   // this wavefront's 8 KB
     if (decltype(partial)::value) {
       int krel;
       const unsigned off = lane_off(right, j, krel);
-      src = k0 + krel < K ? sbase + (size_t)off : zero;
+      const uint16_t* src = k0 + krel < K ? sbase + (size_t)off : zero;
+      set_m0(lds0 + j * 1024);
+      asm volatile("global_load_lds_dwordx4 %0, off" ::"v"(src) : "memory");
     } else {
-      src = sbase + (size_t)(right ? voB[j] : voA[j]);
+      if (j == 0) set_m0(lds0 + 4096);
+      load_fast(IC<j>{}, right ? voB[j] : voA[j], reinterpret_cast<const char*>(sbase) - 4096);
     }
-    __builtin_amdgcn_global_load_lds(SYMI_GPTR(src), SYMI_LPTR((right ? sB : sA) + wdst + j * 512), 16, 0, 0);
   };
   // ---- fragment reads.  Byte address of this lane's piece inside stage 0 of its operand,
   // everything else (32-row block, 16-deep sub-step, stage) is an immediate offset.
@@ -416,10 +435,18 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, uint16_t* const s
         if (KS == 3) load_frags(IC<bu ^ 1>{}, IC<S ^ 1>{}, IC<0>{}, IC<1>{});
         else load_frags(IC<bu ^ 1>{}, IC<S>{}, IC<(KS + 1) & 3>{}, IC<1>{});
       }
-#pragma unroll
-      for (int u = 0; u < LPI; ++u) {
-        if (KS == 3) dma_one(cA, cB, (step + 2) * BK, LPI * i + u, partial);
-        else if (KS == 0) dma_one(oA, oB, (step + 1) * BK, 8 + LPI * i + u, partial);
+      // phase 3: the left operand of step + 2 into the stage just freed; phase 0: the right one
+      auto issue = [&](auto uc) {
+        constexpr int U = decltype(uc)::value;
+        if (i == 0) { if (KS == 3) dma_one(cA, cB, (step + 2) * BK, IC<0 * LPI + U>{}, partial); else dma_one(oA, oB, (step + 1) * BK, IC<8 + 0 * LPI + U>{}, partial); }
+        if (i == 1) { if (KS == 3) dma_one(cA, cB, (step + 2) * BK, IC<1 * LPI + U>{}, partial); else dma_one(oA, oB, (step + 1) * BK, IC<8 + 1 * LPI + U>{}, partial); }
+        if (MI == 4 && i == 2) { if (KS == 3) dma_one(cA, cB, (step + 2) * BK, IC<(2 * LPI + U) & 7>{}, partial); else dma_one(oA, oB, (step + 1) * BK, IC<8 + ((2 * LPI + U) & 7)>{}, partial); }
+        if (MI == 4 && i == 3) { if (KS == 3) dma_one(cA, cB, (step + 2) * BK, IC<(3 * LPI + U) & 7>{}, partial); else dma_one(oA, oB, (step + 1) * BK, IC<8 + ((3 * LPI + U) & 7)>{}, partial); }
+      };
+      if (KS == 3 || KS == 0) {
+        issue(IC<0>{});
+        issue(IC<1>{});
+        if (LPI == 4) { issue(IC<2>{}); issue(IC<3>{}); }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -434,20 +461,24 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, uint16_t* const s
     phase(IC<2>{}, IC<1>{}, t + 1, partial);
     phase(IC<3>{}, IC<1>{}, t + 1, partial);
   };
-  if (K >= 2 * BK) {
-#pragma unroll
-    for (int q = 0; q < 16; ++q) dma_one(sA0, sB0, 0, q, std::false_type{});
-#pragma unroll
-    for (int q = 0; q < 8; ++q) dma_one(sA1, sB1, BK, q, std::false_type{});
-  } else {
-#pragma unroll
-    for (int q = 0; q < 16; ++q) dma_one(sA0, sB0, 0, q, std::true_type{});
-#pragma unroll
-    for (int q = 0; q < 8; ++q) dma_one(sA1, sB1, BK, q, std::true_type{});
-  }
-  // step 0 has landed, the half of step 1 may still fly: 8 loads, or the 4 of a wavefront that
-  // skips the left operand (the others then wait for 4 loads of step 1 as well)
-  if (MI == 4) __builtin_amdgcn_s_waitcnt(0x0F78); else __builtin_amdgcn_s_waitcnt(0x0F74);
+  auto prologue = [&](auto partial) {
+    auto all16 = [&](uint16_t* a, uint16_t* b, int k0, auto halfc) {
+      dma_one(a, b, k0, IC<0>{}, partial); dma_one(a, b, k0, IC<1>{}, partial); dma_one(a, b, k0, IC<2>{}, partial);
+      dma_one(a, b, k0, IC<3>{}, partial); dma_one(a, b, k0, IC<4>{}, partial); dma_one(a, b, k0, IC<5>{}, partial);
+      dma_one(a, b, k0, IC<6>{}, partial); dma_one(a, b, k0, IC<7>{}, partial);
+      if (decltype(halfc)::value) return;
+      dma_one(a, b, k0, IC<8>{}, partial); dma_one(a, b, k0, IC<9>{}, partial); dma_one(a, b, k0, IC<10>{}, partial);
+      dma_one(a, b, k0, IC<11>{}, partial); dma_one(a, b, k0, IC<12>{}, partial); dma_one(a, b, k0, IC<13>{}, partial);
+      dma_one(a, b, k0, IC<14>{}, partial); dma_one(a, b, k0, IC<15>{}, partial);
+    };
+    all16(sA0, sB0, 0, std::false_type{});   // step 0, both operands
+    all16(sA1, sB1, BK, std::true_type{});   // step 1, left operand (the right one follows in phase 0)
+  };
+  if (K >= 2 * BK) prologue(std::false_type{}); else prologue(std::true_type{});
+  // step 0 has landed, the left operand of step 1 (8 loads) may still fly; in a half-height
+  // tile the wavefronts that skip the left operand have nothing of step 1 in flight: all wait
+  // for everything there
+  if (MI == 4) __builtin_amdgcn_s_waitcnt(0x0F78); else wait_vmcnt0();
   __builtin_amdgcn_s_barrier();
   load_frags(IC<0>{}, IC<0>{}, IC<0>{}, IC<2>{});
   // always pairs of steps: for an odd step count the second stage holds the zeros of the
