@@ -5,9 +5,10 @@
 //   symi_ceiling_mfma        16 independent MFMA 32x32x16 bf16 chains per wavefront, operands in
 //                            registers: the rate of the matrix pipes alone with the given data
 //   symi_ceiling_gemm_loop   the reduction loop of the grouped GEMM (256x256 tile, 64-deep steps,
-//                            direct-to-LDS loads into two stages, fragment reads by hand, four
-//                            phases of 16 MFMAs) on a plain C = A B^T, whole or with one of its
-//                            three ingredients taken out
+//                            direct-to-LDS loads into two stages in the scalar-base form with one
+//                            M0 write per operand and stage, fragment reads by hand, four phases
+//                            of 16 MFMAs) on a plain C = A B^T, whole or with one of its three
+//                            ingredients taken out
 //   symi_ceiling_adam_streams the Adam step's memory streams (4 fp32 reads, 3 fp32 writes, bf16
 //                            replica writes) without the optimizer's meaning, in three layouts
 // All pointers are device pointers of the caller, all launches go to the caller's stream.
@@ -78,22 +79,29 @@ __global__ __launch_bounds__(256) void gemm_loop_kernel(const uint16_t* __restri
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int lrow = lane >> 3, pch = lane & 7;
-  const uint16_t* ag[2];
-  const uint16_t* bg[2];
+  // the loads in the form the grouped GEMM uses: scalar base (operand + step, 4 KB low), 32-bit
+  // per-lane byte offset, immediate; the LDS base (M0) written once per operand and stage
+  unsigned vo[2][8];
 #pragma unroll
-  for (int par = 0; par < 2; ++par) {
+  for (int j = 0; j < 8; ++j) {
+    const int par = j & 1;
     const int kc = pch ^ ((4 * par + (lane >> 4)) & 7);
-    ag[par] = A + (long long)(m0 + wave * 64 + par * 8 + lrow) * K + kc * 8;
-    bg[par] = B + (long long)(n0 + wave * 64 + par * 8 + lrow) * K + kc * 8;
+    const long long rowA = m0 + wave * 64 + par * 8 + lrow + (j >> 1) * 16, rowB = n0 + wave * 64 + par * 8 + lrow + (j >> 1) * 16;
+    vo[0][j] = (unsigned)((rowA * K + kc * 8) * 2 + 4096 - (j - 4) * 1024);
+    vo[1][j] = (unsigned)((rowB * K + kc * 8) * 2 + 4096 - (j - 4) * 1024);
   }
-  const int wbase = wave * 64 * BK;
-  // q = 0..15: instruction j = q >> 1 of the right (odd q) or left operand
-  auto dma_q = [&](uint16_t* sA, uint16_t* sB, int k0, int q) {
-    const int j = q >> 1;
-    if (q & 1)
-      __builtin_amdgcn_global_load_lds(GPTR(bg[j & 1] + (long long)(j >> 1) * 16 * K + k0), LPTR(sB + wbase + j * 8 * BK), 16, 0, 0);
-    else
-      __builtin_amdgcn_global_load_lds(GPTR(ag[j & 1] + (long long)(j >> 1) * 16 * K + k0), LPTR(sA + wbase + j * 8 * BK), 16, 0, 0);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  // q = 0..7: instruction q of the left operand, 8..15: instruction q - 8 of the right one
+  auto dma_q = [&](uint16_t* sA, uint16_t* sB, int k0, auto qc) {
+    constexpr int Q = decltype(qc)::value, j = Q & 7;
+    constexpr bool right = Q >= 8;
+    if (j == 0) {
+      const unsigned l = (unsigned)(size_t)LPTR((right ? sB : sA) + wave_u * 64 * BK + 4 * 8 * BK);
+      asm volatile("s_mov_b32 m0, %0" ::"s"(l) : "memory");
+    }
+    const char* sb = reinterpret_cast<const char*>(right ? B : A) + (long long)k0 * 2 - 4096;   // wave-uniform
+    const unsigned v = vo[right ? 1 : 0][j];
+    asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(v), "s"(sb), "n"((j - 4) * 1024) : "memory");
   };
   floatx16 acc[4][4];
 #pragma unroll
@@ -143,9 +151,16 @@ __global__ __launch_bounds__(256) void gemm_loop_kernel(const uint16_t* __restri
         if (MFMA) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[bu][j], fa[bu][i], acc[i][j], 0, 0, 0);
         else asm volatile("" :: "v"(fb[bu][j]), "v"(fa[bu][i]));
       }
-      if (DMA) {
-        if (KS == 3) { dma_q(cA, cB, (t + 2) * BK, 2 * i); dma_q(cA, cB, (t + 2) * BK, 2 * i + 1); }
-        else if (KS == 0) { dma_q(oA, oB, (t + 1) * BK, 8 + 2 * i); dma_q(oA, oB, (t + 1) * BK, 8 + 2 * i + 1); }
+      if (DMA && (KS == 3 || KS == 0)) {
+        auto two = [&](auto ic) {
+          constexpr int I = decltype(ic)::value;
+          if (KS == 3) { dma_q(cA, cB, (t + 2) * BK, IC<2 * I>{}); dma_q(cA, cB, (t + 2) * BK, IC<2 * I + 1>{}); }
+          else { dma_q(oA, oB, (t + 1) * BK, IC<8 + 2 * I>{}); dma_q(oA, oB, (t + 1) * BK, IC<8 + 2 * I + 1>{}); }
+        };
+        if (i == 0) two(IC<0>{});
+        if (i == 1) two(IC<1>{});
+        if (i == 2) two(IC<2>{});
+        if (i == 3) two(IC<3>{});
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -153,10 +168,14 @@ __global__ __launch_bounds__(256) void gemm_loop_kernel(const uint16_t* __restri
   const int nk = K / BK;   // even
   // the loop prefetches two steps ahead: A and B carry one tile of slack rows behind them
   // (the host checks the buffer sizes), so the loads of steps nk, nk+1 stay in bounds
-#pragma unroll
-  for (int q = 0; q < 16; ++q) dma_q(sA0, sB0, 0, q);
-#pragma unroll
-  for (int q = 0; q < 8; ++q) dma_q(sA1, sB1, BK, q);
+  auto eight = [&](uint16_t* a, uint16_t* b, int k0, auto basec) {
+    constexpr int Q0 = decltype(basec)::value;
+    dma_q(a, b, k0, IC<Q0 + 0>{}); dma_q(a, b, k0, IC<Q0 + 1>{}); dma_q(a, b, k0, IC<Q0 + 2>{}); dma_q(a, b, k0, IC<Q0 + 3>{});
+    dma_q(a, b, k0, IC<Q0 + 4>{}); dma_q(a, b, k0, IC<Q0 + 5>{}); dma_q(a, b, k0, IC<Q0 + 6>{}); dma_q(a, b, k0, IC<Q0 + 7>{});
+  };
+  eight(sA0, sB0, 0, IC<0>{});
+  eight(sA0, sB0, 0, IC<8>{});
+  eight(sA1, sB1, BK, IC<0>{});
   __builtin_amdgcn_s_waitcnt(0x0F78);
   __builtin_amdgcn_s_barrier();
   load_frags(IC<0>{}, aad[0][0], bad[0][0]);

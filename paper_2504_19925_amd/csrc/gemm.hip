@@ -557,20 +557,26 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, uint16_t* const s
       // consecutive hidden units of one row, combines them with the saved u and v (16 bytes
       // each, whole lines per instruction) and writes du = dh v s (1 + u (1 - s)),
       // dv = dh u s, s = sigmoid(u).  The u, v loads of block i + 1 are issued before block i
-      // is worked on, so their latency hides behind it.
+      // is worked on, so their latency hides behind it.  They are unconditional: a lane past
+      // the tile's last row or column reads the last valid row / the last 8 columns instead
+      // (its result is never stored).  A load under a branch would make the compiler lose
+      // count of the memory operations in flight and wait for all of them, the stores of the
+      // previous rows included, before every use of a loaded value.
       float* const sf = reinterpret_cast<float*>(stg);
       const uint16_t* UVi = static_cast<const uint16_t*>(p.UV);
       uint16_t* Co = static_cast<uint16_t*>(p.C);
       const int col = n0 + wn * 128 + (lane & 15) * 8;
+      const int colc = min(col, p.N - 8);
+      const int twof = 2 * p.f;
       auto load_uv = [&](int blk, uint4 (&uu)[8], uint4 (&vv)[8]) {
+        const int rb = row0 + wm * WROWS + blk * 32;
+        const uint16_t* const q0 = UVi + (long long)rb * twof + colc;
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
-          const int row = row0 + wm * WROWS + blk * 32 + it * 4 + (lane >> 4);
-          if (row < row1 && col < p.N) {
-            const long long o = (long long)row * 2 * p.f + col;
-            uu[it] = *reinterpret_cast<const uint4*>(UVi + o);
-            vv[it] = *reinterpret_cast<const uint4*>(UVi + o + p.f);
-          }
+          const int dr = min(rb + it * 4 + (lane >> 4), row1 - 1) - rb;   // may be negative
+          const uint16_t* const q = q0 + (long long)dr * twof;
+          uu[it] = *reinterpret_cast<const uint4*>(q);
+          vv[it] = *reinterpret_cast<const uint4*>(q + p.f);
         }
       };
       if (i == 0) load_uv(0, uvu[0], uvv[0]);
