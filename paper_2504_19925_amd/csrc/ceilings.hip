@@ -273,6 +273,8 @@ int symi_ceiling_gemm_loop(int variant, const void* A, const void* B, void* C, i
                            long long a_elems, long long b_elems, void* stream) {
   if (!A || !B || !C || M < 256 || N < 256 || K < 128 || M % 256 || N % 256 || K % 128) return -1;
   if (a_elems < (long long)(M + 256) * K || b_elems < (long long)(N + 256) * K) return -1;
+  // the per-lane byte offsets of the loads are 32 bits wide
+  if ((long long)(M + 256) * K * 2 >= (1LL << 32) || (long long)(N + 256) * K * 2 >= (1LL << 32)) return -1;
   const dim3 grid(N / BN, M / BM);
   hipStream_t st = (hipStream_t)stream;
   const uint16_t* a = (const uint16_t*)A;

@@ -670,6 +670,22 @@ __device__ __forceinline__ void gemm_tile(const GemmParams& p, uint16_t* const s
   }
 }
 
+// Workgroups go to the eight XCDs (each with an L2 of its own) round robin in launch order:
+// workgroup b runs on XCD b mod 8.  With the column index fastest an XCD would see two (ntx = 16)
+// or one (ntx = 4) column tile of every m-tile, so every activation tile is fetched by four to
+// eight L2s.  Instead a round of R consecutive workgroups (R / 8 per XCD, R / ntx m-tiles) is dealt
+// out in blocks: XCD c takes 4 column tiles x R / 32 m-tiles, so an operand tile along either
+// edge of the block is fetched by that L2 once for the whole block.  b -> tile is a permutation
+// inside the round; the caller leaves rounds that are not whole in launch order.
+__device__ __forceinline__ void xcd_block(int b, int ntx, int R, int& tile) {
+  if (ntx != 4 && ntx != 8 && ntx != 16 && ntx != 32) return;
+  const int l = b % R, c = l & 7, s = l >> 3;
+  const int xn = ntx >> 2;   // XCDs side by side along the columns
+  const int n = 4 * (c % xn) + (s & 3);
+  const int m = (b / R) * (R / ntx) + (R >> 5) * (c / xn) + (s >> 2);
+  tile = m * ntx + n;
+}
+
 template <int MODE>
 __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
   __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * BM * BK + 2 * BN * BK];
@@ -686,6 +702,7 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
     int full = n_tiles, sl = 1;
     if ((MODE == FWD2 || MODE == BWD_DX) && p.partials) tail_slices(n_tiles, p.cus, p.K, full, sl);
     int tile = b;
+    if (b < (full & ~255)) xcd_block(b, ntx, 256, tile);
     if (b >= full) {
       tile = full + (b - full) / sl;
       zsl = (b - full) % sl;
@@ -709,7 +726,15 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
     // classes in order of decreasing row count: the long reductions start first and the
     // short (or empty, store-only) tiles fill in behind them
     group = p.per_slot ? blockIdx.z : p.class_order[blockIdx.z];
-    row0 = blockIdx.y * BM;
+    // the tiles of one class (or slot): whole rounds of 256, 128 or 64 workgroups are dealt out
+    // in blocks per XCD (a group starts on XCD 0 whenever its tile count is a multiple of 8)
+    const int ntx = gridDim.x, nt = ntx * gridDim.y;
+    int tile = blockIdx.y * ntx + blockIdx.x;
+    const int R = nt % 256 == 0 ? 256 : nt % 128 == 0 ? 128 : nt % 64 == 0 ? 64 : 0;
+    if (R) xcd_block(tile, ntx, R, tile);
+    const int mt = tile / ntx;
+    bx = tile - mt * ntx;
+    row0 = mt * BM;
     row1 = min(p.M, row0 + BM);
     if (p.per_slot) {   // the rows of one replica slot
       kbeg = p.slot_offsets[group];
