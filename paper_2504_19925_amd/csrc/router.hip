@@ -146,6 +146,22 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
     }
   };
 
+  // R_DX adds into dX: the old values of the whole tile are requested before the reduction
+  // starts, in the layout the epilogue works in (a lane: 8 consecutive columns of a row), so
+  // that their latency is paid once, next to the first operand loads.  The loads carry no
+  // branch (lanes past the edge read the last row / the last 8 columns; never stored).
+  uint4 old[2][4];
+  if (MODE == R_DX && (N & 7) == 0) {
+    const uint16_t* const dXp = static_cast<const uint16_t*>(p.dX);
+    const int col = min(n0 + wn * 64 + (lane & 7) * 8, N - 8);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int row = min(m0 + wm * 64 + i * 32 + it * 8 + (lane >> 3), M - 1);
+        old[i][it] = *reinterpret_cast<const uint4*>(dXp + (long long)row * N + col);
+      }
+  }
   if (kbeg < kend) fetch(kbeg);
   for (int k0 = kbeg; k0 < kend; k0 += RK) {
     commit();
@@ -213,13 +229,12 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
         const float4 x0 = *reinterpret_cast<const float4*>(stg + rr * LDT + (lane & 7) * 8);
         const float4 x1 = *reinterpret_cast<const float4*>(stg + rr * LDT + (lane & 7) * 8 + 4);
         if (row < M && col < N) {
-          uint4* o = reinterpret_cast<uint4*>(dXp + (long long)row * N + col);
-          const uint4 old = *o;
-          *o = make_uint4(
-              pack_bf16x2(__uint_as_float(old.x << 16) + x0.x, __uint_as_float(old.x & 0xffff0000u) + x0.y),
-              pack_bf16x2(__uint_as_float(old.y << 16) + x0.z, __uint_as_float(old.y & 0xffff0000u) + x0.w),
-              pack_bf16x2(__uint_as_float(old.z << 16) + x1.x, __uint_as_float(old.z & 0xffff0000u) + x1.y),
-              pack_bf16x2(__uint_as_float(old.w << 16) + x1.z, __uint_as_float(old.w & 0xffff0000u) + x1.w));
+          const uint4 o = old[i][it];
+          *reinterpret_cast<uint4*>(dXp + (long long)row * N + col) = make_uint4(
+              pack_bf16x2(__uint_as_float(o.x << 16) + x0.x, __uint_as_float(o.x & 0xffff0000u) + x0.y),
+              pack_bf16x2(__uint_as_float(o.y << 16) + x0.z, __uint_as_float(o.y & 0xffff0000u) + x0.w),
+              pack_bf16x2(__uint_as_float(o.z << 16) + x1.x, __uint_as_float(o.z & 0xffff0000u) + x1.y),
+              pack_bf16x2(__uint_as_float(o.w << 16) + x1.z, __uint_as_float(o.w & 0xffff0000u) + x1.w));
         }
       }
       __builtin_amdgcn_s_waitcnt(0xC07F);   // the next block's writes must not pass these reads
@@ -281,24 +296,48 @@ __global__ __launch_bounds__(256) void router_reduce_kernel(const float* __restr
   }
 }
 
-// db[e] = sum_t dl[t,e] in two fixed-order stages: per chunk of 256 tokens (threads along
-// e, so every row is read contiguously), then over the chunks
+// db[e] = sum_t dl[t,e] in two fixed-order stages: per chunk of 256 tokens, then over the
+// chunks.  First stage: threads along e (every row is read contiguously), and where E < 256
+// the rows of the chunk are dealt out over 256 / E groups of threads whose sums are added in
+// group order; eight independent loads in flight per thread.
 __global__ __launch_bounds__(256) void router_bias_partial_kernel(const float* __restrict__ dl, int T, int E,
                                                                   float* __restrict__ part) {
+  __shared__ double red[256];
+  const int tid = threadIdx.x;
   const int t0 = blockIdx.x * 256, t1 = min(T, t0 + 256);
-  for (int e = threadIdx.x; e < E; e += 256) {
+  const int cols = min(E, 256), groups = 256 / cols;
+  const int g = tid / cols, ec = tid - g * cols;
+  for (int eb = 0; eb < E; eb += cols) {   // the same trip count for every thread
+    const int e = eb + ec;
     double s = 0.0;   // the summands cancel heavily: accumulate in binary64
-    for (int t = t0; t < t1; ++t) s += (double)dl[(long long)t * E + e];
-    part[(long long)blockIdx.x * E + e] = (float)s;
+    if (g < groups && e < E) {
+#pragma unroll 8
+      for (int t = t0 + g; t < t1; t += groups) s += (double)dl[(long long)t * E + e];
+    }
+    red[tid] = s;
+    __syncthreads();
+    if (g == 0 && e < E) {
+      for (int q = 1; q < groups; ++q) s += red[q * cols + ec];
+      part[(long long)blockIdx.x * E + e] = (float)s;
+    }
+    __syncthreads();
   }
 }
+// Second stage, one workgroup per class: thread c adds chunks c, c + 256, ... in ascending
+// order, then the 256 sums are added pairwise in a fixed tree.
 __global__ __launch_bounds__(256) void router_bias_final_kernel(const float* __restrict__ part, int nchunk,
                                                                 int E, float* __restrict__ db) {
-  const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e >= E) return;
+  __shared__ double red[256];
+  const int e = blockIdx.x, tid = threadIdx.x;
   double s = 0.0;
-  for (int c = 0; c < nchunk; ++c) s += (double)part[(long long)c * E + e];
-  db[e] = (float)s;
+  for (int c = tid; c < nchunk; c += 256) s += (double)part[(long long)c * E + e];
+  red[tid] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) red[tid] += red[tid + w];
+    __syncthreads();
+  }
+  if (tid == 0) db[e] = (float)red[0];
 }
 
 // ---- fp32 configurations: one output element per thread, plain FMAs in index order
@@ -401,7 +440,7 @@ extern "C" int symi_router_bwd(const symi_ctx* ctx, const void* X, const void* W
     const int nb = cdiv(T, 256);
     if (nb > 0)
       SYMI_TIMED(ctx, K_ROUTER_DW, st, (router_bias_partial_kernel<<<nb, 256, 0, st>>>(dlogits, T, E, part)));
-    SYMI_TIMED(ctx, K_ROUTER_DW, st, (router_bias_final_kernel<<<cdiv(E, 256), 256, 0, st>>>(part, nb, E, db)));
+    SYMI_TIMED(ctx, K_ROUTER_DW, st, (router_bias_final_kernel<<<E, 256, 0, st>>>(part, nb, E, db)));
   }
   SYMI_LAUNCH_CHECK("symi_router_bwd");
   return SYMI_OK;
