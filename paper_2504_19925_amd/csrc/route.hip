@@ -16,6 +16,7 @@
 namespace symi {
 
 constexpr int ROUTE_THREADS = 256;
+constexpr int ROUTE_THREADS_MAX = 1024;   // route_kernel on large batches
 constexpr int MAX_K = 16;
 
 __global__ void fill_i32_kernel(int32_t* p, int n, int32_t val) {
@@ -78,18 +79,22 @@ constexpr int KEY_NONE = INT_MIN;
 // increasing column order with a strict comparison (so the lowest column wins ties inside a
 // lane without comparing columns), skips the values retired in earlier rounds by a bit mask, and
 // settles the winner across the group by a butterfly over (key, column) pairs.
+// Workgroups of 256 or 1024 threads (blockDim.x): every workgroup adds its histogram to the
+// global one with E atomics, so a large batch takes the large workgroup (a quarter of the
+// atomics on the same E addresses).
 template <int G, int NV>
-__global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
+__global__ __launch_bounds__(ROUTE_THREADS_MAX) void route_kernel(
     const float* __restrict__ logits, int32_t* __restrict__ idx, float* __restrict__ gate,
     int32_t* __restrict__ hist, int T, int E, int k, int renorm) {
   extern __shared__ int32_t hist_s[];
-  for (int i = threadIdx.x; i < E; i += ROUTE_THREADS) hist_s[i] = 0;
+  const int nthreads = blockDim.x;
+  for (int i = threadIdx.x; i < E; i += nthreads) hist_s[i] = 0;
   __syncthreads();
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane & (G - 1), sub = lane / G;
   constexpr int tpw = 64 / G;
-  constexpr int tpb = (ROUTE_THREADS / 64) * tpw;
+  const int tpb = (nthreads / 64) * tpw;
   constexpr int NVAL = NV * 4;
   auto col_of = [&](int c) { return ((c >> 2) * G + g) * 4 + (c & 3); };
 
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < E; i += ROUTE_THREADS)
+  for (int i = threadIdx.x; i < E; i += nthreads)
     if (hist_s[i]) atomicAdd(&hist[i], hist_s[i]);
 }
 
@@ -266,11 +271,14 @@ extern "C" int symi_route(const symi_ctx* ctx, const float* logits, int32_t* idx
   if (cfg->T > 0) {
     int G, NV;
     route_fwd_shape(E, cfg->T, G, NV);
-    const int grid = route_grid(cfg->T, G);
+    int grid = route_grid(cfg->T, G);
+    // four workgroups of 256 per compute unit or more: one of 1024 each instead
+    const int threads = grid >= 4 * ctx->cus ? ROUTE_THREADS_MAX : ROUTE_THREADS;
+    if (threads == ROUTE_THREADS_MAX) grid = cdiv(grid, ROUTE_THREADS_MAX / ROUTE_THREADS);
     const size_t sh = (size_t)E * sizeof(int32_t);
 #define SYMI_ROUTE_CASE(GG, NN)                                                                  \
   case GG * 16 + NN:                                                                             \
-    SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<GG, NN><<<grid, ROUTE_THREADS, sh, st>>>(          \
+    SYMI_TIMED(ctx, K_ROUTE, st, (route_kernel<GG, NN><<<grid, threads, sh, st>>>(          \
         logits, idx, gate, hist, cfg->T, E, cfg->k, cfg->renorm)));                              \
     break;
 #define SYMI_ROUTE_G(GG) SYMI_ROUTE_CASE(GG, 1) SYMI_ROUTE_CASE(GG, 2) SYMI_ROUTE_CASE(GG, 4) SYMI_ROUTE_CASE(GG, 8)
