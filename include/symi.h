@@ -39,7 +39,7 @@
  *     E <= S_tot <= 4096, P_e divisible by N, 0 <= shard < N; d, f and P_e/N
  *     multiples of 8.  Beyond the launch limits of the kernels (SYMI_EUNSUPPORTED):
  *     T*k/256 + S_tot + 256 <= 65535 m-tiles (fp32: 4*(T*k/256 + S_tot) <= 65535),
- *     T/128 <= 65535, 2*f*d < 2^31.
+ *     T/128 <= 65535, 2*f*d <= 2^31 - 8192, d <= 2^22, f <= 2^21.
  */
 #ifndef SYMI_H
 #define SYMI_H

@@ -58,7 +58,10 @@ int check_cfg(const symi_cfg* c, const char* who) {
   UNSUPPORTED(c->dtype == SYMI_BF16 ? mtiles + 256 > 65535 : 4 * mtiles > 65535,
               "T*k/256 + S_tot (m-tiles of the grouped GEMM; four times that for fp32) exceeds the grid limit");
   UNSUPPORTED(((long long)c->T + 127) / 128 > 65535, "T/128 exceeds the grid limit of the router kernels");
-  UNSUPPORTED(2LL * c->f * c->d >= (1LL << 31), "2*f*d must stay below 2^31");
+  // the grouped GEMM addresses an operand tile with 32-bit per-lane byte offsets (8 KB of bias
+  // included): a weight panel spans up to 2*f*d elements, 256 tile rows up to 256*max(d, 2f)
+  UNSUPPORTED(2LL * c->f * c->d > (1LL << 31) - 8192, "2*f*d must not exceed 2^31 - 8192");
+  UNSUPPORTED(c->d > (1 << 22) || c->f > (1 << 21), "d must not exceed 2^22 and f 2^21");
 #undef UNSUPPORTED
   return SYMI_OK;
 }

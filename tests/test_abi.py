@@ -109,7 +109,10 @@ def test_launch_limits_are_rejected_as_unsupported():
     for bad in (dict(ok, T=1 << 22, k=4),                 # 65536 + 16 + 256 m-tiles
                 dict(ok, dtype="f32"),                    # fp32 tiles are a quarter the rows
                 dict(ok, T=(1 << 23) + 1024, k=1, E=1, S_tot=1),   # T / 128 > 65535
-                dict(ok, T=64, d=1 << 16, f=1 << 14)):    # 2*f*d = 2^31
+                dict(ok, T=64, d=1 << 16, f=1 << 14),     # 2*f*d = 2^31
+                dict(ok, T=64, d=8, f=(1 << 27) - 8),     # 2*f*d = 2^31 - 128: no room for the offset bias
+                dict(ok, T=64, d=1 << 23, f=8),           # 256 rows of d elements pass 2^32 bytes
+                dict(ok, T=64, d=8, f=1 << 22)):          # ... of 2f elements
         assert symi.symi_validate(_cfg(**bad)) == -2, bad
         assert symi.symi_workspace_bytes(_cfg(**bad)) == 0
 
