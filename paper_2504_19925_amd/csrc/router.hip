@@ -9,9 +9,13 @@
 // are plain 16-byte reads) or reduction-strided (LDS tile [k][row] as in memory, fragments come
 // from the transposing LDS read ds_read_b64_tr_b16); several workgroups per compute unit hide
 // the latency.
-// The weight gradient's reduction runs over all T tokens: it is cut into chunks of 512
-// tokens whose partial products are summed by a second kernel in a fixed order.
+// The weight gradient's reduction runs over all T tokens: it is cut into chunks of at least
+// 512 tokens whose partial products are summed by a second kernel in a fixed order.
+// With E <= 128 (a multiple of 8) the two backward products run in one kernel that reads X,
+// dX and dlogits once (router_bwd_fused_kernel below); other E take the shared kernel twice.
 // fp32 configurations take a plain FMA kernel (one output per thread) instead.
+#include <type_traits>
+
 #include "common.h"
 
 namespace symi {
@@ -286,6 +290,219 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
   }
 }
 
+// ---- both backward products in one pass (bf16, E <= 128 and a multiple of 8)
+// Workgroup = one column tile of 128 (of d) x one chunk of tokens, walked in row blocks of 128:
+//   dX[t, n] += sum_e dl[t, e] Wr[e, n]      (reduction over the classes)
+//   dWr[e, n] += sum_t dl[t, e] X[t, n]      (reduction over the block's tokens, kept in the
+//                                             accumulators over the whole chunk)
+// The column tile of Wr stays in LDS; a block of dlogits is fetched and converted once and
+// serves both products (read along e for the first, transposed for the second); X, the old dX
+// values and the dlogits of the next block are in flight while the current one is worked on.
+// Every global load is unconditional (clamped address, value zeroed where it must not count), so
+// the compiler can count the loads in flight instead of waiting for all of them.
+typedef unsigned int ru32x4 __attribute__((ext_vector_type(4)));
+constexpr int FSD = RT + 8;     // dlogits block [t][e]: 272-byte rows (plain 16-byte reads are conflict-free)
+constexpr int FSW = RT + 32;    // Wr and X tiles [k][n]: 320-byte rows (transposing reads are conflict-free)
+
+__global__ __launch_bounds__(256) void router_bwd_fused_kernel(RouterParams p) {
+  __shared__ __attribute__((aligned(16))) uint16_t DLt[RT * FSD];
+  __shared__ __attribute__((aligned(16))) uint16_t WRt[RT * FSW];
+  __shared__ __attribute__((aligned(16))) uint16_t XT[RT * FSW];   // later the epilogue's staging
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int T = p.T, E = p.E, d = p.d;
+  const int n0 = blockIdx.x * RT;
+  const int t_beg = blockIdx.y * p.chunk, t_end = min(T, t_beg + p.chunk);
+  const uint16_t* const X = static_cast<const uint16_t*>(p.X);
+  const uint16_t* const Wr = static_cast<const uint16_t*>(p.Wr);
+  uint16_t* const dX = static_cast<uint16_t*>(p.dX);
+
+  // piece u = tid + 256 h (h < 8) of a 128 x 128 tile: row u / 16, 8 consecutive columns at 8 (u % 16)
+  const int pr = tid >> 4, pc = (tid & 15) * 8;       // row of piece h: pr + 16 h
+  const int ncol = min(n0 + pc, d - 8);               // clamped: columns past d are never stored
+  const int ecol = min(pc, E - 8);
+  const bool e_ok = pc < E;
+  // epilogue layout of the dX tile: block i (32 rows), pass it: row 8 it + lane / 8, 8 columns
+  const int ocol = min(n0 + wn * 64 + (lane & 7) * 8, d - 8);
+
+  // Wr tile, once: rows e >= E are zero
+#pragma unroll
+  for (int h = 0; h < 8; ++h) {
+    const int e = pr + 16 * h;
+    uint4 w = *reinterpret_cast<const uint4*>(Wr + (long long)min(e, E - 1) * d + ncol);
+    if (e >= E) w = make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(&WRt[e * FSW + pc]) = w;
+  }
+
+  float4 rd[8][2];   // dlogits pieces (fp32) of the block being fetched
+  ru32x4 rx[8];      // X pieces
+  uint4 ro[2][4];    // old dX values
+  auto fetch = [&](int t0) __attribute__((always_inline)) {   // requested while the previous block is worked on
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+      const long long t = min(t0 + pr + 16 * h, T - 1);
+      const float* q = p.dl + t * E + ecol;
+      rd[h][0] = *reinterpret_cast<const float4*>(q);
+      rd[h][1] = *reinterpret_cast<const float4*>(q + 4);
+      rx[h] = *reinterpret_cast<const ru32x4*>(X + t * d + ncol);
+    }
+  };
+  auto fetch_old = [&](int t0) __attribute__((always_inline)) {   // requested behind the previous block's stores
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const long long t = min(t0 + wm * 64 + i * 32 + it * 8 + (lane >> 3), T - 1);
+        ro[i][it] = *reinterpret_cast<const uint4*>(dX + t * d + ocol);
+      }
+  };
+
+  rfloatx16 accw[2][2];   // dWr tile of the chunk
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) accw[i][j][r] = 0.f;
+
+  // fragments: plain = [row][k] tile, a lane reads 8 k of row lane % 32; transposing = [k][row]
+  // tile, lane 16 g + jj addresses k-row 8 (g >> 1) + jj / 4 (+4 for the second half), the
+  // 8-byte piece jj % 4 of rows 16 (g & 1) .., and receives row lane % 32's 4 + 4 k-values
+  auto frag_plain = [&](const uint16_t* tile, int stride, int rbase, int ks) __attribute__((always_inline)) -> rbf16x8 {
+    return *reinterpret_cast<const rbf16x8*>(&tile[(rbase + (lane & 31)) * stride + ks * 16 + 8 * (lane >> 5)]);
+  };
+  auto frag_tr = [&](const uint16_t* tile, int stride, int rbase, int ks) __attribute__((always_inline)) -> rbf16x8 {
+    const int g = lane >> 4, jj = lane & 15;
+    const uint16_t* q = tile + (16 * ks + 8 * (g >> 1) + (jj >> 2)) * stride + rbase + 16 * (g & 1) + 4 * (jj & 3);
+    const rshortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) rshortx4*)((void __attribute__((address_space(3)))*)(q)));
+    const rshortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) rshortx4*)((void __attribute__((address_space(3)))*)(q + 4 * stride)));
+    union { rshortx4 h[2]; rbf16x8 v; } u;
+    u.h[0] = lo;
+    u.h[1] = hi;
+    return u.v;
+  };
+
+  // one row block; FULL: all its rows and columns exist and another block follows, so neither
+  // the stores of the epilogue nor the requests for the next block sit under a branch (behind a
+  // branch the compiler no longer knows how many memory operations are in flight, and every
+  // wait for a loaded value becomes a wait for everything issued so far)
+  auto block = [&](int t0, auto fullc) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(fullc)::value;
+    // this block's operands to LDS; rows past T and classes past E count as zero
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+      const bool ok = e_ok && t0 + pr + 16 * h < T;
+      uint4 v = make_uint4(pack_bf16x2(rd[h][0].x, rd[h][0].y), pack_bf16x2(rd[h][0].z, rd[h][0].w),
+                           pack_bf16x2(rd[h][1].x, rd[h][1].y), pack_bf16x2(rd[h][1].z, rd[h][1].w));
+      if (!ok) v = make_uint4(0, 0, 0, 0);
+      *reinterpret_cast<uint4*>(&DLt[(pr + 16 * h) * FSD + pc]) = v;
+      *reinterpret_cast<ru32x4*>(&XT[(pr + 16 * h) * FSW + pc]) = rx[h];
+    }
+    __syncthreads();
+    if (FULL || t0 + RT < t_end) fetch(t0 + RT);   // in flight during the MFMAs and the epilogue
+
+    rfloatx16 accx[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accx[i][j][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < RT / 16; ++ks) {
+      rbf16x8 af[2], bfr[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = frag_plain(DLt, FSD, wm * 64 + i * 32, ks);
+        bfr[i] = frag_tr(WRt, FSW, wn * 64 + i * 32, ks);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          accx[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], accx[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int ks = 0; ks < RT / 16; ++ks) {
+      rbf16x8 af[2], bfr[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = frag_tr(DLt, FSD, wm * 64 + i * 32, ks);
+        bfr[i] = frag_tr(XT, FSW, wn * 64 + i * 32, ks);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          accw[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], accw[i][j], 0, 0, 0);
+    }
+    __syncthreads();   // nobody reads XT any more: it becomes the staging area
+
+    // dX += : a lane owns output row lane % 32 of a 32 x 32 block and 4 columns per group of 8;
+    // every wavefront turns its 32 x 64 blocks around through a private part of XT so that a lane
+    // handles 8 consecutive columns of a row and a store instruction covers 8 rows x 128 bytes
+    constexpr int LDT = 68;
+    float* const stg = reinterpret_cast<float*>(XT) + wave * (32 * LDT);
+    const int r32 = lane & 31, hw = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(stg + r32 * LDT + 32 * j + 8 * g + 4 * hw) =
+              make_float4(accx[i][j][4 * g], accx[i][j][4 * g + 1], accx[i][j][4 * g + 2], accx[i][j][4 * g + 3]);
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): wavefront-private area
+      const int col = n0 + wn * 64 + (lane & 7) * 8;
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int rr = it * 8 + (lane >> 3);
+        const int row = t0 + wm * 64 + i * 32 + rr;
+        const float4 x0 = *reinterpret_cast<const float4*>(stg + rr * LDT + (lane & 7) * 8);
+        const float4 x1 = *reinterpret_cast<const float4*>(stg + rr * LDT + (lane & 7) * 8 + 4);
+        if (FULL || (row < T && col < d)) {
+          const uint4 o = ro[i][it];
+          *reinterpret_cast<uint4*>(dX + (long long)row * d + col) = make_uint4(
+              pack_bf16x2(__uint_as_float(o.x << 16) + x0.x, __uint_as_float(o.x & 0xffff0000u) + x0.y),
+              pack_bf16x2(__uint_as_float(o.y << 16) + x0.z, __uint_as_float(o.y & 0xffff0000u) + x0.w),
+              pack_bf16x2(__uint_as_float(o.z << 16) + x1.x, __uint_as_float(o.z & 0xffff0000u) + x1.y),
+              pack_bf16x2(__uint_as_float(o.w << 16) + x1.z, __uint_as_float(o.w & 0xffff0000u) + x1.w));
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // the next block's writes must not pass these reads
+    }
+    if (FULL || t0 + RT < t_end) fetch_old(t0 + RT);
+    __syncthreads();   // the staging area is XT again
+  };
+  if (t_beg < t_end) {
+    fetch(t_beg);
+    fetch_old(t_beg);
+  }
+  int t0 = t_beg;
+  if (n0 + RT <= d)
+    for (; t0 + 2 * RT <= t_end; t0 += RT) block(t0, std::true_type{});
+  for (; t0 < t_end; t0 += RT) block(t0, std::false_type{});
+
+  // the chunk's partial weight gradient: row e = lane % 32 of each 32 x 32 block, 4 columns per group
+  float* const part = p.partial + (long long)blockIdx.y * E * d;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int e = wm * 64 + i * 32 + (lane & 31);
+    if (e >= E) continue;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
+        if (col < d)   // d is a multiple of 8: the four columns are inside together
+          *reinterpret_cast<float4*>(part + (long long)e * d + col) =
+              make_float4(accw[i][j][4 * g], accw[i][j][4 * g + 1], accw[i][j][4 * g + 2], accw[i][j][4 * g + 3]);
+      }
+  }
+}
+
 // dWr[e,n] = sum over chunks of partial[chunk,e,n], chunks in ascending order
 __global__ __launch_bounds__(256) void router_reduce_kernel(const float* __restrict__ partial, int nchunk,
                                                             long long n, float* __restrict__ dWr) {
@@ -420,9 +637,19 @@ extern "C" int symi_router_bwd(const symi_ctx* ctx, const void* X, const void* W
     const int tiles = cdiv(d, RT) * cdiv(E, RT);
     int chunk = RCHUNK;
     while ((long long)cdiv(T, chunk) * tiles > 1024 && chunk < 16384) chunk *= 2;
+    const bool fused = E <= RT && E % 8 == 0;
+    if (fused) {
+      // one workgroup per compute unit at a time (its LDS): as many chunks as give every unit
+      // one workgroup, each then walks its row blocks with the next one in flight
+      const int per = std::max(1, ctx->cus / cdiv(d, RT));
+      chunk = std::max(RCHUNK, cdiv(cdiv(T, per), RT) * RT);
+    }
     p.chunk = chunk;
     const int nchunk = cdiv(T, chunk);
-    if (T > 0) {
+    if (T > 0 && fused) {
+      // both products in one pass over X, dX and dlogits
+      SYMI_TIMED(ctx, K_ROUTER_DX, st, (router_bwd_fused_kernel<<<dim3(cdiv(d, RT), nchunk), 256, 0, st>>>(p)));
+    } else if (T > 0) {
       SYMI_TIMED(ctx, K_ROUTER_DX, st, (router_gemm_kernel<R_DX><<<dim3(cdiv(d, RT), cdiv(T, RT)), 256, 0, st>>>(p)));
       SYMI_TIMED(ctx, K_ROUTER_DW, st, (router_gemm_kernel<R_DW><<<dim3(cdiv(d, RT), cdiv(E, RT), nchunk), 256, 0, st>>>(p)));
     }
