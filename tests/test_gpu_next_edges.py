@@ -22,6 +22,8 @@ def _cases(dtype):
         wl.scaled(base, T=130, E=3, k=1, S_tot=64, N=4, d=40, f=72),        # most slots empty
         wl.scaled(base, T=257, E=23, k=2, S_tot=46, N=2, d=72, f=200),      # E odd: scalar router stores
         wl.scaled(base, T=0, E=8, k=2, S_tot=16, N=4, d=128, f=256),        # empty batch
+        wl.scaled(base, T=77, E=16, k=3, S_tot=16, N=2, d=24, f=40),        # one partial router row block and column tile
+        wl.scaled(base, T=1300, E=8, k=2, S_tot=8, N=2, d=136, f=16),       # three router chunks, ragged last block, 8 columns in the second tile
         wl.scaled(base, T=700, E=130, k=5, S_tot=260, N=2, d=64, f=64, router_matmul=False,
                   bias="zipf", zipf_s=1.2),                                  # E > 128: two router column tiles
     ]
