@@ -29,6 +29,7 @@ constexpr int RLD = RK + 8;    // padded LDS row of a [row][k] tile (elements; 1
 constexpr int RLS = RT + 32;   // padded LDS row of a [k][row] tile (320 B: four k-rows cover 64 banks)
 constexpr int RTILE = RT * RLD > RK * RLS ? RT * RLD : RK * RLS;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short rshortx4;
+typedef unsigned int ru32x4 __attribute__((ext_vector_type(4)));
 constexpr int RCHUNK = 512;    // tokens per partial weight gradient, at least
 
 enum { R_FWD = 0, R_DX = 1, R_DW = 2 };
@@ -166,11 +167,8 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
         old[i][it] = *reinterpret_cast<const uint4*>(dXp + (long long)row * N + col);
       }
   }
-  if (kbeg < kend) fetch(kbeg);
-  for (int k0 = kbeg; k0 < kend; k0 += RK) {
-    commit();
-    __syncthreads();
-    if (k0 + RK < kend) fetch(k0 + RK);   // in flight while this step feeds the MFMAs
+  // the MFMAs of one 64-deep step from the two LDS tiles
+  auto mma = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int ks = 0; ks < RK / 16; ++ks) {
       rbf16x8 af[2], bfr[2];
@@ -202,7 +200,65 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     }
-    __syncthreads();
+  };
+  if constexpr (MODE == R_FWD) {
+    // The forward streams X once with few workgroups per compute unit (T / 128 of them): two
+    // steps are kept in flight in two register sets.  Every load is unconditional (clamped
+    // address; pieces past the reduction's end are zeroed on both sides, rows past the tile's
+    // edge only reach outputs that are never stored) and the steps come in pairs, so the loop
+    // has no branch and the wait for one set's loads does not wait for the other's.
+    const uint16_t* const Xb = static_cast<const uint16_t*>(p.X);
+    const uint16_t* const Wb = static_cast<const uint16_t*>(p.Wr);
+    ru32x4 xa[2][4], xb[2][4];
+    auto fetch2 = [&](auto setc, int k0) __attribute__((always_inline)) {
+      constexpr int S = decltype(setc)::value;
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        const int u = tid + 256 * h;
+        const int kp = k0 + 8 * (u & 7), kc = min(kp, kend - 8);
+        xa[S][h] = *reinterpret_cast<const ru32x4*>(Xb + (long long)min(m0 + (u >> 3), M - 1) * p.d + kc);
+        xb[S][h] = *reinterpret_cast<const ru32x4*>(Wb + (long long)min(n0 + (u >> 3), N - 1) * p.d + kc);
+      }
+    };
+    auto commit2 = [&](auto setc, int k0) __attribute__((always_inline)) {
+      constexpr int S = decltype(setc)::value;
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        const int u = tid + 256 * h;
+        const bool in = k0 + 8 * (u & 7) < kend;   // the values are only looked at here
+        const ru32x4 zero = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<ru32x4*>(&As[(u >> 3) * RLD + 8 * (u & 7)]) = in ? xa[S][h] : zero;
+        *reinterpret_cast<ru32x4*>(&Bs[(u >> 3) * RLD + 8 * (u & 7)]) = in ? xb[S][h] : zero;
+      }
+    };
+    const int nk2 = ((kend - kbeg + RK - 1) / RK + 1) / 2 * 2;
+    fetch2(std::integral_constant<int, 0>{}, kbeg);
+    fetch2(std::integral_constant<int, 1>{}, kbeg + RK);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int s2 = 0; s2 < nk2; s2 += 2) {
+      const int k0 = kbeg + s2 * RK;
+      commit2(std::integral_constant<int, 0>{}, k0);
+      __syncthreads();
+      fetch2(std::integral_constant<int, 0>{}, k0 + 2 * RK);
+      __builtin_amdgcn_sched_barrier(0);   // the requests go out here, not behind the MFMAs
+      mma();
+      __syncthreads();
+      commit2(std::integral_constant<int, 1>{}, k0 + RK);
+      __syncthreads();
+      fetch2(std::integral_constant<int, 1>{}, k0 + 3 * RK);
+      __builtin_amdgcn_sched_barrier(0);
+      mma();
+      __syncthreads();
+    }
+  } else {
+    if (kbeg < kend) fetch(kbeg);
+    for (int k0 = kbeg; k0 < kend; k0 += RK) {
+      commit();
+      __syncthreads();
+      if (k0 + RK < kend) fetch(k0 + RK);   // in flight while this step feeds the MFMAs
+      mma();
+      __syncthreads();
+    }
   }
 
   // a lane owns output row lane%32 of each 32 x 32 block and, per 8-column group g, the 4
@@ -300,7 +356,6 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(RouterParams p) {
 // values and the dlogits of the next block are in flight while the current one is worked on.
 // Every global load is unconditional (clamped address, value zeroed where it must not count), so
 // the compiler can count the loads in flight instead of waiting for all of them.
-typedef unsigned int ru32x4 __attribute__((ext_vector_type(4)));
 constexpr int FSD = RT + 8;     // dlogits block [t][e]: 272-byte rows (plain 16-byte reads are conflict-free)
 constexpr int FSW = RT + 32;    // Wr and X tiles [k][n]: 320-byte rows (transposing reads are conflict-free)
 
