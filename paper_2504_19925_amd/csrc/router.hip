@@ -389,17 +389,21 @@ __global__ __launch_bounds__(256) void router_bwd_fused_kernel(RouterParams p) {
     *reinterpret_cast<uint4*>(&WRt[e * FSW + pc]) = w;
   }
 
-  float4 rd[8][2];   // dlogits pieces (fp32) of the block being fetched
-  ru32x4 rx[8];      // X pieces
-  uint4 ro[2][4];    // old dX values
-  auto fetch = [&](int t0) __attribute__((always_inline)) {   // requested while the previous block is worked on
+  // two register sets: while block b is worked on, the operands of blocks b + 1 and b + 2 are
+  // on their way (one set would leave a block's requests only the time of one block's MFMAs
+  // and epilogue to arrive)
+  float4 rd[2][8][2];   // dlogits pieces (fp32)
+  ru32x4 rx[2][8];      // X pieces
+  uint4 ro[2][4];       // old dX values
+  auto fetch = [&](auto setc, int t0) __attribute__((always_inline)) {
+    constexpr int S = decltype(setc)::value;
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
       const long long t = min(t0 + pr + 16 * h, T - 1);
       const float* q = p.dl + t * E + ecol;
-      rd[h][0] = *reinterpret_cast<const float4*>(q);
-      rd[h][1] = *reinterpret_cast<const float4*>(q + 4);
-      rx[h] = *reinterpret_cast<const ru32x4*>(X + t * d + ncol);
+      rd[S][h][0] = *reinterpret_cast<const float4*>(q);
+      rd[S][h][1] = *reinterpret_cast<const float4*>(q + 4);
+      rx[S][h] = *reinterpret_cast<const ru32x4*>(X + t * d + ncol);
     }
   };
   auto fetch_old = [&](int t0) __attribute__((always_inline)) {   // requested behind the previous block's stores
@@ -443,20 +447,22 @@ __global__ __launch_bounds__(256) void router_bwd_fused_kernel(RouterParams p) {
   // the stores of the epilogue nor the requests for the next block sit under a branch (behind a
   // branch the compiler no longer knows how many memory operations are in flight, and every
   // wait for a loaded value becomes a wait for everything issued so far)
-  auto block = [&](int t0, auto fullc) __attribute__((always_inline)) {
+  auto block = [&](int t0, auto fullc, auto setc) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(fullc)::value;
+    constexpr int S = decltype(setc)::value;
     // this block's operands to LDS; rows past T and classes past E count as zero
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
       const bool ok = e_ok && t0 + pr + 16 * h < T;
-      uint4 v = make_uint4(pack_bf16x2(rd[h][0].x, rd[h][0].y), pack_bf16x2(rd[h][0].z, rd[h][0].w),
-                           pack_bf16x2(rd[h][1].x, rd[h][1].y), pack_bf16x2(rd[h][1].z, rd[h][1].w));
+      uint4 v = make_uint4(pack_bf16x2(rd[S][h][0].x, rd[S][h][0].y), pack_bf16x2(rd[S][h][0].z, rd[S][h][0].w),
+                           pack_bf16x2(rd[S][h][1].x, rd[S][h][1].y), pack_bf16x2(rd[S][h][1].z, rd[S][h][1].w));
       if (!ok) v = make_uint4(0, 0, 0, 0);
       *reinterpret_cast<uint4*>(&DLt[(pr + 16 * h) * FSD + pc]) = v;
-      *reinterpret_cast<ru32x4*>(&XT[(pr + 16 * h) * FSW + pc]) = rx[h];
+      *reinterpret_cast<ru32x4*>(&XT[(pr + 16 * h) * FSW + pc]) = rx[S][h];
     }
     __syncthreads();
-    if (FULL || t0 + RT < t_end) fetch(t0 + RT);   // in flight during the MFMAs and the epilogue
+    if (FULL || t0 + 2 * RT < t_end) fetch(setc, t0 + 2 * RT);   // in flight for the next two blocks
+    __builtin_amdgcn_sched_barrier(0);   // the requests go out here, not behind the MFMAs
 
     rfloatx16 accx[2][2];
 #pragma unroll
@@ -531,14 +537,26 @@ __global__ __launch_bounds__(256) void router_bwd_fused_kernel(RouterParams p) {
     if (FULL || t0 + RT < t_end) fetch_old(t0 + RT);
     __syncthreads();   // the staging area is XT again
   };
+  const std::integral_constant<int, 0> set0;
+  const std::integral_constant<int, 1> set1;
   if (t_beg < t_end) {
-    fetch(t_beg);
+    fetch(set0, t_beg);
     fetch_old(t_beg);
+    fetch(set1, t_beg + RT);   // clamped to existing rows if there is no second block
   }
   int t0 = t_beg;
-  if (n0 + RT <= d)
-    for (; t0 + 2 * RT <= t_end; t0 += RT) block(t0, std::true_type{});
-  for (; t0 < t_end; t0 += RT) block(t0, std::false_type{});
+  if (n0 + RT <= d)   // pairs of full blocks that are followed by two more blocks
+    for (; t0 + 3 * RT < t_end; t0 += 2 * RT) {
+      block(t0, std::true_type{}, set0);
+      block(t0 + RT, std::true_type{}, set1);
+    }
+  while (t0 < t_end) {
+    block(t0, std::false_type{}, set0);
+    t0 += RT;
+    if (t0 >= t_end) break;
+    block(t0, std::false_type{}, set1);
+    t0 += RT;
+  }
 
   // the chunk's partial weight gradient: row e = lane % 32 of each 32 x 32 block, 4 columns per group
   float* const part = p.partial + (long long)blockIdx.y * E * d;
