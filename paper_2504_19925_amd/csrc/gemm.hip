@@ -702,7 +702,17 @@ __global__ __launch_bounds__(GT) void gemm_bf16_kernel(GemmParams p) {
     int full = n_tiles, sl = 1;
     if ((MODE == FWD2 || MODE == BWD_DX) && p.partials) tail_slices(n_tiles, p.cus, p.K, full, sl);
     int tile = b;
-    if (b < (full & ~255)) xcd_block(b, ntx, 256, tile);
+    if (ntx == 4 || ntx == 8 || ntx == 16 || ntx == 32) {
+      if (b < (full & ~255)) xcd_block(b, ntx, 256, tile);
+    } else if (ntx < 32) {
+      // other column counts: rounds of 8 m-tiles, XCD c takes all column tiles of the round's
+      // m-tile c (launch order would scatter an m-tile's columns over all eight L2s)
+      const int R = 8 * ntx;
+      if (b < full - full % R) {
+        const int l = b % R;
+        tile = (b / R * 8 + (l & 7)) * ntx + (l >> 3);
+      }
+    }
     if (b >= full) {
       tile = full + (b - full) / sl;
       zsl = (b - full) % sl;
