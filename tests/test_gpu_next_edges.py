@@ -81,6 +81,10 @@ def test_router_capacity_and_replica_path_on_edge_shapes(dtype):
         if c.T:
             check_close("dX_total", Hn.npf(s.dX), dX_e + o_dXr, c.dtype)
             check_close("dWr", Hn.npf(dWr), o_dWr, c.dtype)
+            # stage-isolated: the library's own dlogits through the oracle's router backward
+            i_dWr, i_db, _ = O.router_backward(Xn, Wn, Hn.npf(s.dlogits))
+            check_close("dWr_isolated", Hn.npf(dWr), i_dWr, c.dtype)
+            check_close("db_isolated", Hn.npf(db), i_db, "f32")
         else:
             assert not dWr.any() and not db.any()
         # ---- the all-reduce over the replicas, average over the class's replicas
